@@ -1,0 +1,259 @@
+/*
+ * CPU oracle for the ViDiT-Q quantized linear layer.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, obviously
+ * correct statement of what the quantized linear layer computes, used only by
+ * the test-suite, the smoke check and the CPU-baseline leg of the benchmark.
+ * It shares no source, header, table or helper with the HIP library.
+ *
+ * What it follows (ViDiT-Q, arxiv 2406.02540):
+ *   - Sec. 3.1, Eq. 2: uniform b-bit quantizer x_int = clamp(round(x / s) + z).
+ *     Used here in its symmetric form (z = 0, s = absmax / (2^(b-1) - 1),
+ *     integers in [-(2^(b-1)-1), 2^(b-1)-1]), so the min-max range is
+ *     [-absmax, absmax] and nothing is clipped.
+ *   - Sec. 4.1: one parameter set per token for activations, computed online
+ *     from the token itself (dynamic), and one per output channel for weights.
+ *   - Sec. 4.2, Eq. 3: scaling-based channel balancing
+ *     Y = (X diag(s)^-1)(diag(s) W); the activation side receives
+ *     chan_mul[k] = 1/s_k, the weight side is multiplied by s_k before it is
+ *     quantized.
+ *   - Appendix "Hardware implementation of quantized linear layers": integer
+ *     products are summed along the input channels first, the two scales
+ *     (s_x of the token, s_w of the output channel) multiply the integer sum
+ *     afterwards.
+ *   - Appendix "Performance under lower bitwidth": W4A8 stores 4-bit weights
+ *     and widens them to 8 bits for the same integer contraction.
+ *
+ * Arithmetic fixed where the paper is silent (every fp32 operation is rounded
+ * on its own, round-to-nearest-even, no fused multiply-add, no reassociation;
+ * build with -ffp-contract=off -fno-fast-math):
+ *   - token statistics in fp32: t = float(x_f16) * chan_mul[k];
+ *     amax = max |t|; x_scale = amax / 127; inv = 127 / amax (one reciprocal
+ *     per token); q = clamp(rint(t * inv), -127, 127); rint rounds halves to
+ *     even; a token of zeros gives x_scale = 0 and q = 0.
+ *   - weights the same way per output channel with qmax 127 (int8) or 7 (int4).
+ *   - the integer sum is taken in int64 and must fit int32.
+ *   - y = fp16_rne( ((float)acc * x_scale[m]) * w_scale[n] + float(bias[n]) ).
+ *
+ * Matrices are dense row-major: X[M,K], W[N,K] (K contiguous), Y[M,N].
+ * fp16 values travel as uint16_t bit patterns.
+ *
+ * Every function here is pinned by tests that do not go through this file
+ * (hand examples, closed-form error bounds, symmetries, brute-force sums,
+ * numpy's own float16 conversion); none is "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG 1
+#define ORACLE_ERR_OVERFLOW 2
+
+/* ---- IEEE binary16 <-> binary32, written out bit by bit ------------------ */
+
+/* Exact widening of a binary16 bit pattern. */
+float oracle_half_to_float(uint16_t h) {
+    uint32_t sign = (uint32_t)(h >> 15) & 1u;
+    uint32_t exp = (uint32_t)(h >> 10) & 0x1Fu;
+    uint32_t man = (uint32_t)h & 0x3FFu;
+    double v;
+    if (exp == 0) {
+        v = ldexp((double)man, -24);            /* zero and subnormals: man * 2^-24 */
+    } else if (exp == 31) {
+        v = man ? (double)NAN : (double)INFINITY;
+    } else {
+        v = ldexp((double)(man + 1024u), (int)exp - 25); /* (1 + man/1024) * 2^(exp-15) */
+    }
+    return (float)(sign ? -v : v);
+}
+
+/* Narrowing with round-to-nearest-even; overflow goes to infinity (no saturation). */
+uint16_t oracle_float_to_half(float f) {
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    uint16_t sign = (uint16_t)((bits >> 16) & 0x8000u);
+    double a = fabs((double)f);
+    if (isnan(f)) return (uint16_t)(sign | 0x7E00u);
+    if (a == 0.0) return sign;
+    /* The spacing of binary16 values around a: 2^(e-10) for normal range,
+       2^-24 below 2^-14.  Dividing by it and rounding to an integer with
+       ties-to-even (rint in the default rounding mode) is the RNE narrowing. */
+    int e;
+    (void)frexp(a, &e);          /* a = m * 2^e, m in [0.5, 1)  ->  a in [2^(e-1), 2^e) */
+    int ulp_exp = (e - 1) - 10;  /* exponent of one unit in the last place */
+    if (ulp_exp < -24) ulp_exp = -24;
+    double n = rint(ldexp(a, -ulp_exp)); /* integer count of ulps, exact in double */
+    double r = ldexp(n, ulp_exp);        /* the rounded value */
+    if (r >= 65520.0) return (uint16_t)(sign | 0x7C00u); /* beyond the largest finite + half ulp */
+    if (isinf(f)) return (uint16_t)(sign | 0x7C00u);
+    /* encode r */
+    if (r < ldexp(1.0, -14)) {
+        return (uint16_t)(sign | (uint16_t)ldexp(r, 24)); /* subnormal: mantissa = r / 2^-24 */
+    }
+    int re;
+    double rm = frexp(r, &re);                 /* r = rm * 2^re, rm in [0.5,1) */
+    uint32_t mant = (uint32_t)ldexp(rm, 11) - 1024u; /* (2*rm - 1) * 1024 */
+    uint32_t bexp = (uint32_t)(re - 1 + 15);
+    return (uint16_t)(sign | (bexp << 10) | mant);
+}
+
+/* ---- Sec. 4.1 + Eq. 2 + Eq. 3: dynamic per-token activation quantizer ---- */
+
+int oracle_quantize_per_token(const uint16_t* x_f16, const float* chan_mul,
+                              int8_t* xq, float* x_scale, int64_t M, int64_t K) {
+    if (!x_f16 || !xq || !x_scale || M < 0 || K <= 0) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t* row = x_f16 + m * K;
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = oracle_half_to_float(row[k]);
+            if (chan_mul) t = t * chan_mul[k];      /* X diag(s)^-1, Eq. 3 */
+            float a = fabsf(t);
+            if (a > amax) amax = a;
+        }
+        float scale = 0.0f, inv = 0.0f;
+        if (amax != 0.0f) {
+            scale = amax / 127.0f;                  /* s of Eq. 2, symmetric min-max */
+            inv = 127.0f / amax;
+        }
+        x_scale[m] = scale;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = oracle_half_to_float(row[k]);
+            if (chan_mul) t = t * chan_mul[k];
+            float q = rintf(t * inv);               /* round to nearest, halves to even */
+            if (q > 127.0f) q = 127.0f;
+            if (q < -127.0f) q = -127.0f;
+            xq[m * K + k] = (int8_t)q;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ---- Sec. 4.1 + Eq. 2 + Eq. 3: per-output-channel weight quantizer ------- */
+
+int oracle_quantize_weight(const float* w, const float* chan_s, int bits,
+                           int8_t* wq, float* w_scale, int64_t N, int64_t K) {
+    if (!w || !wq || !w_scale || N < 0 || K <= 0) return ORACLE_ERR_ARG;
+    if (bits != 8 && bits != 4) return ORACLE_ERR_ARG;
+    const float qmax = (bits == 8) ? 127.0f : 7.0f;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        const float* row = w + n * K;
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = row[k];
+            if (chan_s) t = t * chan_s[k];          /* diag(s) W, Eq. 3 */
+            float a = fabsf(t);
+            if (a > amax) amax = a;
+        }
+        float scale = 0.0f, inv = 0.0f;
+        if (amax != 0.0f) {
+            scale = amax / qmax;
+            inv = qmax / amax;
+        }
+        w_scale[n] = scale;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = row[k];
+            if (chan_s) t = t * chan_s[k];
+            float q = rintf(t * inv);
+            if (q > qmax) q = qmax;
+            if (q < -qmax) q = -qmax;
+            wq[n * K + k] = (int8_t)q;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ---- 4-bit storage: two's-complement nibbles, two per byte along K ------- */
+/* byte j of a row holds k = 2j in bits 0..3 and k = 2j+1 in bits 4..7.       */
+
+int oracle_pack_int4(const int8_t* wq, uint8_t* packed, int64_t N, int64_t K) {
+    if (!wq || !packed || N < 0 || K <= 0 || (K & 1)) return ORACLE_ERR_ARG;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t j = 0; j < K / 2; ++j) {
+            int lo = wq[n * K + 2 * j], hi = wq[n * K + 2 * j + 1];
+            if (lo < -8 || lo > 7 || hi < -8 || hi > 7) return ORACLE_ERR_ARG;
+            packed[n * (K / 2) + j] = (uint8_t)((lo & 0xF) | ((hi & 0xF) << 4));
+        }
+    return ORACLE_OK;
+}
+
+static int8_t nibble_value(unsigned nib) { /* 4-bit two's complement */
+    return (int8_t)((nib & 8u) ? (int)nib - 16 : (int)nib);
+}
+
+int oracle_unpack_int4(const uint8_t* packed, int8_t* wq, int64_t N, int64_t K) {
+    if (!wq || !packed || N < 0 || K <= 0 || (K & 1)) return ORACLE_ERR_ARG;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t j = 0; j < K / 2; ++j) {
+            uint8_t b = packed[n * (K / 2) + j];
+            wq[n * K + 2 * j] = nibble_value(b & 0xFu);
+            wq[n * K + 2 * j + 1] = nibble_value((unsigned)b >> 4);
+        }
+    return ORACLE_OK;
+}
+
+/* ---- integer contraction along the input channels ------------------------ */
+
+int oracle_gemm_i8(const int8_t* xq, const int8_t* wq, int32_t* acc,
+                   int64_t M, int64_t N, int64_t K) {
+    if (!xq || !wq || !acc || M < 0 || N < 0 || K <= 0) return ORACLE_ERR_ARG;
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k)
+                s += (int64_t)xq[m * K + k] * (int64_t)wq[n * K + k];
+            if (s > INT32_MAX || s < INT32_MIN) overflow |= 1;
+            acc[m * N + n] = (int32_t)s;
+        }
+    return overflow ? ORACLE_ERR_OVERFLOW : ORACLE_OK;
+}
+
+/* ---- dequantization: the two scales, then the bias, then fp16 ------------ */
+
+int oracle_dequant(const int32_t* acc, const float* x_scale, const float* w_scale,
+                   const uint16_t* bias_f16, uint16_t* y_f16, int64_t M, int64_t N) {
+    if (!acc || !x_scale || !w_scale || !y_f16 || M < 0 || N < 0) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float yf = (float)acc[m * N + n] * x_scale[m];
+            yf = yf * w_scale[n];
+            if (bias_f16) yf = yf + oracle_half_to_float(bias_f16[n]);
+            y_f16[m * N + n] = oracle_float_to_half(yf);
+        }
+    return ORACLE_OK;
+}
+
+/* ---- the whole layer, steps in the order above ---------------------------
+ * w is int8 [N,K] when w_bits == 8, packed nibbles [N,K/2] when w_bits == 4.
+ * xq_out [M,K], x_scale_out [M] and acc_out [M,N] are caller scratch and are
+ * left filled so that a test can compare the intermediate integers too.
+ * wq_unpacked [N,K] is scratch for the widened weights (used when w_bits == 4).
+ */
+int oracle_linear(const uint16_t* x_f16, const float* chan_mul, const void* w, int w_bits,
+                  const float* w_scale, const uint16_t* bias_f16, uint16_t* y_f16,
+                  int8_t* xq_out, float* x_scale_out, int32_t* acc_out, int8_t* wq_unpacked,
+                  int64_t M, int64_t N, int64_t K) {
+    int rc = oracle_quantize_per_token(x_f16, chan_mul, xq_out, x_scale_out, M, K);
+    if (rc) return rc;
+    const int8_t* wq8;
+    if (w_bits == 8) {
+        wq8 = (const int8_t*)w;
+    } else if (w_bits == 4) {
+        if (!wq_unpacked) return ORACLE_ERR_ARG;
+        rc = oracle_unpack_int4((const uint8_t*)w, wq_unpacked, N, K);
+        if (rc) return rc;
+        wq8 = wq_unpacked;
+    } else {
+        return ORACLE_ERR_ARG;
+    }
+    rc = oracle_gemm_i8(xq_out, wq8, acc_out, M, N, K);
+    if (rc) return rc;
+    return oracle_dequant(acc_out, x_scale_out, w_scale, bias_f16, y_f16, M, N);
+}
