@@ -1,0 +1,145 @@
+/*
+ * vq.h - C ABI of the MI355X (gfx950) quantized linear layer of ViDiT-Q
+ * (arxiv 2406.02540).
+ *
+ * The layer: dynamic per-token symmetric int8 quantization of the activations
+ * with the per-input-channel balancing factor folded in, an int8 x int8 -> int32
+ * contraction along the input channels against per-output-channel int8 (W8A8)
+ * or 4-bit (W4A8) weights, and a dequantization epilogue that multiplies the
+ * integer sum by the token's scale and the output channel's scale, adds the
+ * bias and writes fp16.
+ *
+ * Conventions for every entry point
+ *   - Every pointer is a DEVICE pointer (HIP global memory) unless it says
+ *     "host".  The library never allocates, frees or keeps a pointer: the caller
+ *     owns every buffer.  Outputs must not overlap inputs.
+ *   - Matrices are dense row-major: X[M,K], W[N,K] (the K input channels are
+ *     contiguous), Y[M,N].  fp16 data is IEEE binary16.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  A call validates its arguments on the host, enqueues its
+ *     kernels on that stream and returns without synchronising; outputs are
+ *     valid once the stream has reached that point.
+ *   - Return value: VQ_OK (0) or a vq_status error.  On any error nothing was
+ *     enqueued and no output byte was written.  M == 0 or N == 0 is not an
+ *     error: nothing is enqueued and VQ_OK is returned.
+ *   - Not checked on the device: X and chan_mul finite, chan_mul > 0 and within
+ *     [2^-20, 2^20]; 4-bit weights in [-7, 7].  Violations give unspecified
+ *     values in the outputs, never a fault.
+ *   - Limits: K <= VQ_MAX_K so that |sum| <= K * 127 * 127 fits int32 (also with
+ *     the 4-bit path, which accumulates 16 * w internally).
+ */
+#ifndef VQ_H_
+#define VQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum vq_status {
+    VQ_OK = 0,
+    VQ_ERR_NULL = 1,      /* a required pointer is NULL                               */
+    VQ_ERR_SHAPE = 2,     /* negative size, K == 0, K too large, or K not a multiple
+                             of what the entry point requires                         */
+    VQ_ERR_ALIGN = 3,     /* a base pointer is not 16-byte aligned                    */
+    VQ_ERR_WORKSPACE = 4, /* workspace smaller than vq_linear_workspace_bytes()       */
+    VQ_ERR_LAUNCH = 5,    /* the HIP runtime refused the launch                       */
+    VQ_ERR_ARCH = 6,      /* the current device is not gfx950 (or there is no device) */
+    VQ_ERR_BITS = 7       /* w_bits is neither 8 nor 4                                */
+} vq_status;
+
+#define VQ_MAX_K 131072
+
+/*
+ * Dynamic per-token activation quantizer (Sec. 4.1 "Fine-grained Grouping and
+ * Dynamic Quantization"; quantizer of Sec. 3.1 Eq. 2 in its symmetric form; the
+ * activation half of the channel balancing of Sec. 4.2 Eq. 3).
+ *
+ * For every token m:  t[k] = float(x[m,k]) * chan_mul[k];  amax = max_k |t[k]|;
+ * x_scale[m] = amax / 127;  xq[m,k] = clamp(rne(t[k] * (127 / amax)), -127, 127),
+ * all in fp32, one reciprocal per token, halves rounded to even.  A token of
+ * zeros gives x_scale = 0 and xq = 0.
+ *
+ *   x_f16    in  fp16 [M,K]
+ *   chan_mul in  fp32 [K], the reciprocal 1/s_k of the balancing mask, or NULL
+ *                for no balancing (same as all ones)
+ *   xq       out int8 [M,K]
+ *   x_scale  out fp32 [M]
+ * Any K >= 1 is accepted; rows are processed fastest when K is a multiple of 8.
+ */
+int vq_quantize_per_token(const void* x_f16, const float* chan_mul, int8_t* xq, float* x_scale,
+                          int M, int K, void* hip_stream);
+
+/*
+ * W8A8 integer GEMM with the dequantization epilogue (appendix "Hardware
+ * implementation of quantized linear layers": the integer products are summed
+ * along the input channels, the token-wise and output-channel-wise scales
+ * multiply the sum afterwards; Sec. 5.3 "Hardware Resource Savings").
+ *
+ *   acc[m,n] = sum_k xq[m,k] * wq[n,k]                       (exact, int32)
+ *   y[m,n]   = fp16(float(acc[m,n]) * x_scale[m] * w_scale[n] + float(bias[n]))
+ *
+ *   xq       in  int8 [M,K]          x_scale in fp32 [M]
+ *   wq       in  int8 [N,K]          w_scale in fp32 [N]
+ *   bias_f16 in  fp16 [N] or NULL (no bias)
+ *   y_f16    out fp16 [M,N]
+ *   acc_out  out int32 [M,N] or NULL: a copy of the integer sums, for checking
+ * Requires K % 16 == 0.  Any M, N >= 1; N % 8 == 0 takes the vectorised store path.
+ */
+int vq_gemm_w8a8(const int8_t* xq, const float* x_scale, const int8_t* wq, const float* w_scale,
+                 const void* bias_f16, void* y_f16, int32_t* acc_out,
+                 int M, int N, int K, void* hip_stream);
+
+/*
+ * W4A8: the same contraction and epilogue with 4-bit weights that are widened
+ * to 8 bits on chip before the int8 product (appendix "Performance of ViDiT-Q
+ * under lower bitwidth": 4-bit storage, 8-bit compute).
+ *
+ *   wq4  in uint8 [N,K/2]: byte j of row n holds w[n,2j] in bits 0..3 and
+ *        w[n,2j+1] in bits 4..7, two's-complement nibbles in [-7,7].
+ * Requires K % 32 == 0.  Other arguments as vq_gemm_w8a8; acc_out holds the sums
+ * of the widened weights, i.e. the same integers as the W8A8 routine would give.
+ */
+int vq_gemm_w4a8(const int8_t* xq, const float* x_scale, const uint8_t* wq4, const float* w_scale,
+                 const void* bias_f16, void* y_f16, int32_t* acc_out,
+                 int M, int N, int K, void* hip_stream);
+
+/*
+ * The whole layer: vq_quantize_per_token into the workspace, then the GEMM that
+ * w_bits selects (8: w is int8 [N,K]; 4: w is uint8 [N,K/2] packed as above).
+ *
+ *   workspace  device scratch of at least vq_linear_workspace_bytes(M,N,K,w_bits)
+ *              bytes, 16-byte aligned; holds xq and x_scale between the two
+ *              kernels; contents are unspecified afterwards.
+ */
+int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
+              const float* w_scale, const void* bias_f16, void* y_f16,
+              void* workspace, size_t workspace_bytes, int M, int N, int K, void* hip_stream);
+
+/* Bytes of workspace vq_linear needs (0 if a size is invalid). Host-only, no HIP call. */
+size_t vq_linear_workspace_bytes(int M, int N, int K, int w_bits);
+
+/*
+ * Offline side: per-output-channel symmetric weight quantizer (Sec. 4.1: one
+ * parameter set per output channel; Sec. 4.2 Eq. 3: the weight half of the
+ * channel balancing, W[n,k] * s_k, applied before quantization).
+ *
+ *   w_f32   in  fp32 [N,K]
+ *   chan_s  in  fp32 [K] balancing mask s, or NULL
+ *   w_bits  8: wq_out is int8 [N,K] in [-127,127]
+ *           4: wq_out is uint8 [N,K/2], nibbles in [-7,7] packed as for
+ *              vq_gemm_w4a8 (K must be even)
+ *   w_scale out fp32 [N] = max_k |w[n,k] * s_k| / (127 or 7)
+ */
+int vq_quantize_weight(const float* w_f32, const float* chan_s, int w_bits, void* wq_out,
+                       float* w_scale, int N, int K, void* hip_stream);
+
+/* Static, host-side description of a vq_status value. */
+const char* vq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VQ_H_ */

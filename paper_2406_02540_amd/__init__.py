@@ -1,0 +1,14 @@
+"""MI355X-native quantized linear layer of ViDiT-Q (arxiv 2406.02540).
+
+`binding` wraps the C-ABI library libvidiq.so (hand-written gfx950 kernels);
+`workloads` draws the seeded synthetic DiT-shaped inputs; `build` compiles the library.
+"""
+from .binding import (  # noqa: F401
+    VqError,
+    vq_gemm_w4a8,
+    vq_gemm_w8a8,
+    vq_linear,
+    vq_linear_workspace_bytes,
+    vq_quantize_per_token,
+    vq_quantize_weight,
+)

@@ -1,0 +1,200 @@
+"""Thin Python binding of the C-ABI library libvidiq.so (declared in include/vq.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream, every step of the quantized linear layer runs in the library's kernels.
+There is no fallback: if the library is missing or a call fails, an exception
+is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libvidiq.so")
+
+VQ_OK = 0
+STATUS_NAMES = {0: "VQ_OK", 1: "VQ_ERR_NULL", 2: "VQ_ERR_SHAPE", 3: "VQ_ERR_ALIGN",
+                4: "VQ_ERR_WORKSPACE", 5: "VQ_ERR_LAUNCH", 6: "VQ_ERR_ARCH", 7: "VQ_ERR_BITS"}
+
+# name -> (restype, argtypes); mirrors include/vq.h
+_P, _I, _SZ = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+SIGNATURES = {
+    "vq_quantize_per_token": (_I, [_P, _P, _P, _P, _I, _I, _P]),
+    "vq_gemm_w8a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
+    "vq_gemm_w4a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
+    "vq_linear": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
+    "vq_linear_workspace_bytes": (_SZ, [_I, _I, _I, _I]),
+    "vq_quantize_weight": (_I, [_P, _P, _I, _P, _P, _I, _I, _P]),
+    "vq_status_string": (ctypes.c_char_p, [_I]),
+}
+
+
+class VqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({status_string(status)})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libvidiq.so; raises if it has not been built (python -m paper_2406_02540_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2406_02540_amd.build`")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().vq_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != VQ_OK:
+        raise VqError(status, where)
+
+
+def _dev(t, dtype, name):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: expected a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous (dense row-major)")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def vq_quantize_per_token(x, chan_mul=None, xq=None, x_scale=None, stream=None):
+    """x fp16 [M,K] (+ chan_mul fp32 [K]) -> (xq int8 [M,K], x_scale fp32 [M])."""
+    x = _dev(x, torch.float16, "x")
+    M, K = x.shape
+    chan_mul = _dev(chan_mul, torch.float32, "chan_mul")
+    if chan_mul is not None and tuple(chan_mul.shape) != (K,):
+        raise ValueError("chan_mul must have shape [K]")
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if x_scale is None:
+        x_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
+    _dev(xq, torch.int8, "xq"), _dev(x_scale, torch.float32, "x_scale")
+    if tuple(xq.shape) != (M, K) or tuple(x_scale.shape) != (M,):
+        raise ValueError("output shapes")
+    _check(lib().vq_quantize_per_token(_ptr(x), _ptr(chan_mul), _ptr(xq), _ptr(x_scale), M, K,
+                                       _stream(stream)), "vq_quantize_per_token")
+    return xq, x_scale
+
+
+def _gemm(fn_name, xq, x_scale, w, w_cols_div, w_dtype, w_scale, bias, y, want_acc, stream):
+    xq = _dev(xq, torch.int8, "xq")
+    M, K = xq.shape
+    w = _dev(w, w_dtype, "w")
+    N = w.shape[0]
+    if tuple(w.shape) != (N, K // w_cols_div) or K % w_cols_div:
+        raise ValueError("weight shape does not match K")
+    x_scale = _dev(x_scale, torch.float32, "x_scale")
+    w_scale = _dev(w_scale, torch.float32, "w_scale")
+    bias = _dev(bias, torch.float16, "bias")
+    if tuple(x_scale.shape) != (M,) or tuple(w_scale.shape) != (N,) or \
+            (bias is not None and tuple(bias.shape) != (N,)):
+        raise ValueError("scale / bias shapes")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _dev(y, torch.float16, "y")
+    if tuple(y.shape) != (M, N):
+        raise ValueError("y shape")
+    acc = torch.empty((M, N), dtype=torch.int32, device=xq.device) if want_acc else None
+    _check(getattr(lib(), fn_name)(_ptr(xq), _ptr(x_scale), _ptr(w), _ptr(w_scale), _ptr(bias),
+                                   _ptr(y), _ptr(acc), M, N, K, _stream(stream)), fn_name)
+    return (y, acc) if want_acc else y
+
+
+def vq_gemm_w8a8(xq, x_scale, wq, w_scale, bias=None, y=None, return_acc=False, stream=None):
+    """int8 [M,K] x int8 [N,K] -> fp16 [M,N] (and the int32 sums if return_acc)."""
+    return _gemm("vq_gemm_w8a8", xq, x_scale, wq, 1, torch.int8, w_scale, bias, y, return_acc, stream)
+
+
+def vq_gemm_w4a8(xq, x_scale, wq4, w_scale, bias=None, y=None, return_acc=False, stream=None):
+    """int8 [M,K] x packed 4-bit [N,K/2] -> fp16 [M,N] (and the int32 sums if return_acc)."""
+    return _gemm("vq_gemm_w4a8", xq, x_scale, wq4, 2, torch.uint8, w_scale, bias, y, return_acc,
+                 stream)
+
+
+def vq_linear_workspace_bytes(M, N, K, w_bits) -> int:
+    return int(lib().vq_linear_workspace_bytes(int(M), int(N), int(K), int(w_bits)))
+
+
+def vq_linear(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, workspace=None, stream=None):
+    """The whole layer on fp16 activations; workspace is a uint8 device tensor (allocated if None)."""
+    x = _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if w_bits == 8:
+        w = _dev(w, torch.int8, "w")
+        ok = tuple(w.shape[1:]) == (K,)
+    elif w_bits == 4:
+        w = _dev(w, torch.uint8, "w")
+        ok = K % 2 == 0 and tuple(w.shape[1:]) == (K // 2,)
+    else:
+        raise VqError(7, "vq_linear")
+    if not ok:
+        raise ValueError("weight shape does not match K")
+    N = w.shape[0]
+    chan_mul = _dev(chan_mul, torch.float32, "chan_mul")
+    w_scale = _dev(w_scale, torch.float32, "w_scale")
+    bias = _dev(bias, torch.float16, "bias")
+    if (chan_mul is not None and tuple(chan_mul.shape) != (K,)) or tuple(w_scale.shape) != (N,) \
+            or (bias is not None and tuple(bias.shape) != (N,)):
+        raise ValueError("chan_mul / scale / bias shapes")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    if tuple(y.shape) != (M, N):
+        raise ValueError("y shape")
+    need = vq_linear_workspace_bytes(M, N, K, w_bits)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    _check(lib().vq_linear(_ptr(x), _ptr(chan_mul), _ptr(w), int(w_bits), _ptr(w_scale), _ptr(bias),
+                           _ptr(y), _ptr(workspace), workspace.numel(), M, N, K, _stream(stream)),
+           "vq_linear")
+    return y
+
+
+def vq_quantize_weight(w_f32, chan_s=None, w_bits=8, stream=None):
+    """W fp32 [N,K] (+ s fp32 [K]) -> (wq int8 [N,K] or packed uint8 [N,K/2], w_scale fp32 [N])."""
+    w_f32 = _dev(w_f32, torch.float32, "w")
+    N, K = w_f32.shape
+    chan_s = _dev(chan_s, torch.float32, "chan_s")
+    if chan_s is not None and tuple(chan_s.shape) != (K,):
+        raise ValueError("chan_s must have shape [K]")
+    if w_bits == 8:
+        wq = torch.empty((N, K), dtype=torch.int8, device=w_f32.device)
+    elif w_bits == 4:
+        wq = torch.empty((N, K // 2), dtype=torch.uint8, device=w_f32.device)
+    else:
+        raise VqError(7, "vq_quantize_weight")
+    ws = torch.empty((N,), dtype=torch.float32, device=w_f32.device)
+    _check(lib().vq_quantize_weight(_ptr(w_f32), _ptr(chan_s), int(w_bits), _ptr(wq), _ptr(ws), N, K,
+                                    _stream(stream)), "vq_quantize_weight")
+    return wq, ws

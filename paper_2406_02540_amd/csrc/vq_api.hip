@@ -1,0 +1,171 @@
+// C-ABI front end: argument validation, device check, kernel enqueue.
+// Declarations and the contract of every entry point are in include/vq.h.
+#include <atomic>
+
+#include "vq.h"
+#include "vq_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 16;
+constexpr int kMaxDevices = 64;
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p % kAlign) != 0; }
+
+// 0 = not looked at yet, 1 = gfx950, 2 = something else.  A benign cache: the
+// answer for a device ordinal never changes during the life of the process.
+std::atomic<int> g_arch_state[kMaxDevices];
+
+int check_arch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
+        (void)hipGetLastError();
+        return VQ_ERR_ARCH;
+    }
+    if (dev < kMaxDevices) {
+        const int s = g_arch_state[dev].load(std::memory_order_relaxed);
+        if (s == 1) return VQ_OK;
+        if (s == 2) return VQ_ERR_ARCH;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return VQ_ERR_ARCH;
+    }
+    const char* name = prop.gcnArchName;  // e.g. "gfx950:sramecc+:xnack-"
+    const bool ok = name[0] == 'g' && name[1] == 'f' && name[2] == 'x' && name[3] == '9' &&
+                    name[4] == '5' && name[5] == '0' && (name[6] == '\0' || name[6] == ':');
+    if (dev < kMaxDevices) g_arch_state[dev].store(ok ? 1 : 2, std::memory_order_relaxed);
+    return ok ? VQ_OK : VQ_ERR_ARCH;
+}
+
+int launch_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_LAUNCH; }
+
+int validate_gemm(const void* xq, const void* x_scale, const void* w, const void* w_scale,
+                  const void* bias, const void* y, const void* acc_out, int w_bits, int M, int N,
+                  int K) {
+    if (w_bits != 8 && w_bits != 4) return VQ_ERR_BITS;
+    if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K) return VQ_ERR_SHAPE;
+    if (K % (w_bits == 8 ? 16 : 32) != 0) return VQ_ERR_SHAPE;
+    if (M == 0 || N == 0) return VQ_OK;
+    if (!xq || !x_scale || !w || !w_scale || !y) return VQ_ERR_NULL;
+    if (misaligned(xq) || misaligned(x_scale) || misaligned(w) || misaligned(w_scale) ||
+        misaligned(y) || (bias && misaligned(bias)) || (acc_out && misaligned(acc_out)))
+        return VQ_ERR_ALIGN;
+    return VQ_OK;
+}
+
+int gemm_entry(const int8_t* xq, const float* x_scale, const void* w, int w_bits,
+               const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out, int M,
+               int N, int K, void* hip_stream) {
+    const int v = validate_gemm(xq, x_scale, w, w_scale, bias_f16, y_f16, acc_out, w_bits, M, N, K);
+    if (v != VQ_OK) return v;
+    if (M == 0 || N == 0) return VQ_OK;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_gemm(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, acc_out,
+                                         M, N, K, (hipStream_t)hip_stream));
+}
+
+int validate_quantize(const void* x, const void* chan_mul, const void* xq, const void* x_scale,
+                      int M, int K) {
+    if (M < 0 || K <= 0 || K > VQ_MAX_K) return VQ_ERR_SHAPE;
+    if (M == 0) return VQ_OK;
+    if (!x || !xq || !x_scale) return VQ_ERR_NULL;
+    if (misaligned(x) || misaligned(xq) || misaligned(x_scale) || (chan_mul && misaligned(chan_mul)))
+        return VQ_ERR_ALIGN;
+    return VQ_OK;
+}
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+int vq_quantize_per_token(const void* x_f16, const float* chan_mul, int8_t* xq, float* x_scale,
+                          int M, int K, void* hip_stream) {
+    const int v = validate_quantize(x_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    if (M == 0) return VQ_OK;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_quantize_per_token(x_f16, chan_mul, xq, x_scale, M, K,
+                                                       (hipStream_t)hip_stream));
+}
+
+int vq_gemm_w8a8(const int8_t* xq, const float* x_scale, const int8_t* wq, const float* w_scale,
+                 const void* bias_f16, void* y_f16, int32_t* acc_out, int M, int N, int K,
+                 void* hip_stream) {
+    return gemm_entry(xq, x_scale, wq, 8, w_scale, bias_f16, y_f16, acc_out, M, N, K, hip_stream);
+}
+
+int vq_gemm_w4a8(const int8_t* xq, const float* x_scale, const uint8_t* wq4, const float* w_scale,
+                 const void* bias_f16, void* y_f16, int32_t* acc_out, int M, int N, int K,
+                 void* hip_stream) {
+    return gemm_entry(xq, x_scale, wq4, 4, w_scale, bias_f16, y_f16, acc_out, M, N, K, hip_stream);
+}
+
+size_t vq_linear_workspace_bytes(int M, int N, int K, int w_bits) {
+    if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K || (w_bits != 8 && w_bits != 4)) return 0;
+    // xq [M,K] int8, then x_scale [M] fp32, each rounded up to the alignment
+    return round_up((size_t)M * (size_t)K, kAlign) + round_up((size_t)M * sizeof(float), kAlign);
+}
+
+int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
+              const float* w_scale, const void* bias_f16, void* y_f16, void* workspace,
+              size_t workspace_bytes, int M, int N, int K, void* hip_stream) {
+    if (w_bits != 8 && w_bits != 4) return VQ_ERR_BITS;
+    if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K) return VQ_ERR_SHAPE;
+    if (K % (w_bits == 8 ? 16 : 32) != 0) return VQ_ERR_SHAPE;
+    if (M == 0 || N == 0) return VQ_OK;
+    if (!workspace) return VQ_ERR_NULL;
+    if (misaligned(workspace)) return VQ_ERR_ALIGN;
+    if (workspace_bytes < vq_linear_workspace_bytes(M, N, K, w_bits)) return VQ_ERR_WORKSPACE;
+    int8_t* xq = (int8_t*)workspace;
+    float* x_scale = (float*)((char*)workspace + round_up((size_t)M * (size_t)K, kAlign));
+    // validate both halves before anything is enqueued
+    int v = validate_quantize(x_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    v = validate_gemm(xq, x_scale, w, w_scale, bias_f16, y_f16, nullptr, w_bits, M, N, K);
+    if (v != VQ_OK) return v;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    v = launch_status(vq::launch_quantize_per_token(x_f16, chan_mul, xq, x_scale, M, K, stream));
+    if (v != VQ_OK) return v;
+    return launch_status(vq::launch_gemm(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, nullptr,
+                                         M, N, K, stream));
+}
+
+int vq_quantize_weight(const float* w_f32, const float* chan_s, int w_bits, void* wq_out,
+                       float* w_scale, int N, int K, void* hip_stream) {
+    if (w_bits != 8 && w_bits != 4) return VQ_ERR_BITS;
+    if (N < 0 || K <= 0 || K > VQ_MAX_K) return VQ_ERR_SHAPE;
+    if (w_bits == 4 && (K % 2) != 0) return VQ_ERR_SHAPE;
+    if (N == 0) return VQ_OK;
+    if (!w_f32 || !wq_out || !w_scale) return VQ_ERR_NULL;
+    if (misaligned(w_f32) || misaligned(wq_out) || misaligned(w_scale) ||
+        (chan_s && misaligned(chan_s)))
+        return VQ_ERR_ALIGN;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_quantize_weight(w_f32, chan_s, w_bits, wq_out, w_scale, N, K,
+                                                    (hipStream_t)hip_stream));
+}
+
+const char* vq_status_string(int status) {
+    switch (status) {
+        case VQ_OK: return "ok";
+        case VQ_ERR_NULL: return "a required pointer is NULL";
+        case VQ_ERR_SHAPE: return "invalid or unsupported M, N or K";
+        case VQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case VQ_ERR_WORKSPACE: return "workspace too small";
+        case VQ_ERR_LAUNCH: return "kernel launch failed";
+        case VQ_ERR_ARCH: return "current device is not gfx950";
+        case VQ_ERR_BITS: return "w_bits must be 8 or 4";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

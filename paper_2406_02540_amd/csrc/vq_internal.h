@@ -1,0 +1,21 @@
+// Internal launch interface between the C-ABI front end (vq_api.hip) and the
+// gfx950 kernels.  Every launcher enqueues on `stream` and returns the HIP
+// error of the launch; arguments were validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vq {
+
+hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, int8_t* xq,
+                                     float* x_scale, int M, int K, hipStream_t stream);
+
+hipError_t launch_quantize_weight(const float* w, const float* chan_s, int w_bits, void* wq_out,
+                                  float* w_scale, int N, int K, hipStream_t stream);
+
+// w_bits 8: w is int8 [N,K]; 4: w is packed nibbles [N,K/2].
+hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, int w_bits,
+                       const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out,
+                       int M, int N, int K, hipStream_t stream);
+
+}  // namespace vq

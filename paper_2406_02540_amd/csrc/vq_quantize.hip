@@ -1,0 +1,257 @@
+// Quantizers for gfx950.
+//
+// 1. Dynamic per-token activation quantizer (ViDiT-Q Sec. 4.1; Eq. 2 of Sec. 3.1
+//    in symmetric form; activation side of the channel balancing, Eq. 3 of
+//    Sec. 4.2).  HBM-bound: a token is read once (2 B/element), kept in
+//    registers as fp32 across the absmax reduction, and written once
+//    (1 B/element + one fp32 scale).
+// 2. Offline per-output-channel weight quantizer (same recipe, qmax 127 or 7,
+//    weight side of Eq. 3), with the 4-bit packer fused.
+//
+// This file is compiled with -ffp-contract=off: every fp32 operation rounds on
+// its own, the two divisions per row are the correctly rounded IEEE ones, and
+// rounding to integer is v_rndne_f32 (halves to even).
+#include "vq_internal.h"
+
+namespace vq {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef int int2v __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+constexpr int kQuantThreads = 256;
+constexpr int kRowsPerBlock = kQuantThreads / kWave;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// Rounds to the nearest integer (halves to even), clamps to [-qmax, qmax].
+__device__ __forceinline__ int quantize_one(float t, float inv, float qmax) {
+    float q = __builtin_rintf(t * inv);
+    q = fminf(fmaxf(q, -qmax), qmax);
+    return (int)q;
+}
+
+__device__ __forceinline__ int pack4(int a, int b, int c, int d) {
+    return (a & 0xFF) | ((b & 0xFF) << 8) | ((c & 0xFF) << 16) | (d << 24);
+}
+
+// One wavefront per token.  Lane l owns the 16-byte chunks l, l+64, ... of the
+// row (8 fp16 each), so every load instruction of the wave covers one
+// contiguous 1 KiB piece of the row and every store 512 B.  NCH = chunks per
+// lane = ceil(K/8/64); the row stays in registers between the two passes.
+template <int NCH, bool HAS_MUL>
+__global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave(
+    const half8* __restrict__ x, const float4v* __restrict__ chan_mul, int2v* __restrict__ xq,
+    float* __restrict__ x_scale, int M, int K8) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const long m = (long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    if (m >= M) return;  // whole wavefront leaves together
+    const half8* row = x + m * K8;
+
+    float t[NCH][8];
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = i * kWave + lane;
+        if (c < K8) {
+            const half8 v = __builtin_nontemporal_load(row + c);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[i][j] = (float)v[j];
+            if (HAS_MUL) {
+                const float4v m0 = chan_mul[2 * c], m1 = chan_mul[2 * c + 1];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    t[i][j] = t[i][j] * m0[j];
+                    t[i][4 + j] = t[i][4 + j] * m1[j];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(t[i][j]));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[i][j] = 0.0f;
+        }
+    }
+    amax = wave_max(amax);
+
+    float scale = 0.0f, inv = 0.0f;
+    if (amax != 0.0f) {
+        scale = amax / 127.0f;
+        inv = 127.0f / amax;
+    }
+    if (lane == 0) x_scale[m] = scale;
+
+    int2v* qrow = xq + m * K8;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = i * kWave + lane;
+        if (c < K8) {
+            int q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = quantize_one(t[i][j], inv, 127.0f);
+            int2v o;
+            o.x = pack4(q[0], q[1], q[2], q[3]);
+            o.y = pack4(q[4], q[5], q[6], q[7]);
+            qrow[c] = o;
+        }
+    }
+}
+
+__device__ __forceinline__ float block_max(float v, float* red) {
+    v = wave_max(v);
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    if (lane == 0) red[w] = v;
+    __syncthreads();
+    float r = red[0];
+#pragma unroll
+    for (int i = 1; i < kRowsPerBlock; ++i) r = fmaxf(r, red[i]);
+    __syncthreads();
+    return r;
+}
+
+// Any K, any alignment: one workgroup per token, two passes over the row
+// (the second one hits in cache).  Used when K is not a multiple of 8 or the
+// row does not fit the register-resident kernel.
+template <bool HAS_MUL>
+__global__ __launch_bounds__(kQuantThreads) void quantize_tokens_generic(
+    const _Float16* __restrict__ x, const float* __restrict__ chan_mul, int8_t* __restrict__ xq,
+    float* __restrict__ x_scale, int K) {
+    __shared__ float red[kRowsPerBlock];
+    const long m = blockIdx.x;
+    const _Float16* row = x + m * (long)K;
+    float amax = 0.0f;
+    for (int k = threadIdx.x; k < K; k += kQuantThreads) {
+        float t = (float)row[k];
+        if (HAS_MUL) t = t * chan_mul[k];
+        amax = fmaxf(amax, fabsf(t));
+    }
+    amax = block_max(amax, red);
+    float scale = 0.0f, inv = 0.0f;
+    if (amax != 0.0f) {
+        scale = amax / 127.0f;
+        inv = 127.0f / amax;
+    }
+    if (threadIdx.x == 0) x_scale[m] = scale;
+    int8_t* qrow = xq + m * (long)K;
+    for (int k = threadIdx.x; k < K; k += kQuantThreads) {
+        float t = (float)row[k];
+        if (HAS_MUL) t = t * chan_mul[k];
+        qrow[k] = (int8_t)quantize_one(t, inv, 127.0f);
+    }
+}
+
+// Offline weight quantizer: one workgroup per output channel, fp32 input.
+// BITS == 4 writes two nibbles per byte (k even in bits 0..3, k odd in 4..7).
+template <int BITS, bool HAS_S>
+__global__ __launch_bounds__(kQuantThreads) void quantize_weight_rows(
+    const float* __restrict__ w, const float* __restrict__ chan_s, void* __restrict__ wq_out,
+    float* __restrict__ w_scale, int K) {
+    __shared__ float red[kRowsPerBlock];
+    constexpr float qmax = (BITS == 8) ? 127.0f : 7.0f;
+    const long n = blockIdx.x;
+    const float* row = w + n * (long)K;
+    float amax = 0.0f;
+    for (int k = threadIdx.x; k < K; k += kQuantThreads) {
+        float t = row[k];
+        if (HAS_S) t = t * chan_s[k];
+        amax = fmaxf(amax, fabsf(t));
+    }
+    amax = block_max(amax, red);
+    float scale = 0.0f, inv = 0.0f;
+    if (amax != 0.0f) {
+        scale = amax / qmax;
+        inv = qmax / amax;
+    }
+    if (threadIdx.x == 0) w_scale[n] = scale;
+    if (BITS == 8) {
+        int8_t* qrow = (int8_t*)wq_out + n * (long)K;
+        for (int k = threadIdx.x; k < K; k += kQuantThreads) {
+            float t = row[k];
+            if (HAS_S) t = t * chan_s[k];
+            qrow[k] = (int8_t)quantize_one(t, inv, qmax);
+        }
+    } else {
+        uint8_t* qrow = (uint8_t*)wq_out + n * (long)(K / 2);
+        for (int j = threadIdx.x; j < K / 2; j += kQuantThreads) {
+            float t0 = row[2 * j], t1 = row[2 * j + 1];
+            if (HAS_S) {
+                t0 = t0 * chan_s[2 * j];
+                t1 = t1 * chan_s[2 * j + 1];
+            }
+            const int q0 = quantize_one(t0, inv, qmax), q1 = quantize_one(t1, inv, qmax);
+            qrow[j] = (uint8_t)((q0 & 0xF) | ((q1 & 0xF) << 4));
+        }
+    }
+}
+
+template <int NCH>
+hipError_t launch_wave(const void* x, const float* chan_mul, int8_t* xq, float* x_scale, int M,
+                       int K, hipStream_t stream) {
+    const dim3 grid((unsigned)((M + kRowsPerBlock - 1) / kRowsPerBlock)), block(kQuantThreads);
+    if (chan_mul)
+        hipLaunchKernelGGL((quantize_tokens_wave<NCH, true>), grid, block, 0, stream,
+                           (const half8*)x, (const float4v*)chan_mul, (int2v*)xq, x_scale, M, K / 8);
+    else
+        hipLaunchKernelGGL((quantize_tokens_wave<NCH, false>), grid, block, 0, stream,
+                           (const half8*)x, (const float4v*)nullptr, (int2v*)xq, x_scale, M, K / 8);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, int8_t* xq,
+                                     float* x_scale, int M, int K, hipStream_t stream) {
+    // Register-resident path: rows of 16-byte chunks, at most 16 chunks per lane.
+    const bool vec = (K % 8 == 0) && (K <= 8 * kWave * 16) &&
+                     (((uintptr_t)x_f16 | (uintptr_t)xq) % 16 == 0) &&
+                     (chan_mul == nullptr || (uintptr_t)chan_mul % 16 == 0);
+    if (vec) {
+        const int nch = (K / 8 + kWave - 1) / kWave;
+        switch (nch) {
+            case 1: return launch_wave<1>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 2: return launch_wave<2>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 3: return launch_wave<3>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 4: return launch_wave<4>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 5: return launch_wave<5>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 6: return launch_wave<6>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 7:
+            case 8: return launch_wave<8>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 9: return launch_wave<9>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            case 10:
+            case 11:
+            case 12: return launch_wave<12>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+            default: return launch_wave<16>(x_f16, chan_mul, xq, x_scale, M, K, stream);
+        }
+    }
+    const dim3 grid((unsigned)M), block(kQuantThreads);
+    if (chan_mul)
+        hipLaunchKernelGGL((quantize_tokens_generic<true>), grid, block, 0, stream,
+                           (const _Float16*)x_f16, chan_mul, xq, x_scale, K);
+    else
+        hipLaunchKernelGGL((quantize_tokens_generic<false>), grid, block, 0, stream,
+                           (const _Float16*)x_f16, (const float*)nullptr, xq, x_scale, K);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_weight(const float* w, const float* chan_s, int w_bits, void* wq_out,
+                                  float* w_scale, int N, int K, hipStream_t stream) {
+    const dim3 grid((unsigned)N), block(kQuantThreads);
+#define VQ_LAUNCH_W(BITS, HAS)                                                                  \
+    hipLaunchKernelGGL((quantize_weight_rows<BITS, HAS>), grid, block, 0, stream, w, chan_s, \
+                       wq_out, w_scale, K)
+    if (w_bits == 8) {
+        if (chan_s) VQ_LAUNCH_W(8, true); else VQ_LAUNCH_W(8, false);
+    } else {
+        if (chan_s) VQ_LAUNCH_W(4, true); else VQ_LAUNCH_W(4, false);
+    }
+#undef VQ_LAUNCH_W
+    return hipGetLastError();
+}
+
+}  // namespace vq

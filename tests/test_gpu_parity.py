@@ -1,0 +1,334 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle, element by
+element on the same seeded inputs (bit-exact for int8 codes, scales and int32 sums; fp16
+outputs within 1e-3 relative), on small shapes that span several tiles and ragged tails,
+on the edge cases, and at the full sizes of the five configurations on sampled rows."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from parity_util import assert_fp16_close, freivalds_check  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vq():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2406_02540_amd as pkg
+    from paper_2406_02540_amd import binding
+    binding.lib()  # raises if the HIP library is missing: there is no fallback
+    return pkg
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ---- quantizer -------------------------------------------------------------------------
+
+QUANT_SHAPES = [(1, 8), (5, 64), (37, 1152), (130, 4608), (7, 4096), (3, 8192), (9, 2048),
+                (2, 333), (3, 1), (2, 9000), (4, 8200), (1000, 1152), (6, 520), (3, 3584), (2, 5000)]
+
+
+@pytest.mark.parametrize("M,K", QUANT_SHAPES)
+@pytest.mark.parametrize("with_mul", [False, True])
+def test_quantize_per_token_bit_exact(vq, oracle, M, K, with_mul):
+    say(f"quantize M={M} K={K} mul={with_mul}")
+    g = np.random.default_rng(1000 + M * 7 + K)
+    x = (g.standard_normal((M, K)) * np.exp(g.uniform(-3, 3, (M, 1)))).astype(np.float16)
+    if M > 2:
+        x[1] = 0  # a token of zeros
+    cm = np.exp(g.uniform(np.log(0.25), np.log(4.0), K)).astype(np.float32) if with_mul else None
+    xq_ref, xs_ref = oracle.quantize_per_token(x, cm)
+    xq, xs = vq.vq_quantize_per_token(dev(x), None if cm is None else dev(cm))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(xs).view(np.uint32), xs_ref.view(np.uint32))
+    assert np.array_equal(host(xq), xq_ref)
+
+
+def test_quantize_ties_subnormals_extremes(vq, oracle):
+    say("quantize special values")
+    rows = [
+        [127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 0],
+        [1, -0.5, 0.25, 0, 0, 0, 0, 0],
+        [6e-8, -6e-8, 1.2e-7, 0, 0, 0, 0, 0],
+        [65504, -65504, 1, 32752, 0, 0, 0, 0],
+        [0, 0, 0, 0, 0, 0, 0, 0],
+        [-254, 127, 1, 3, 0, 0, 0, 0],
+    ]
+    x = np.array(rows, np.float16)
+    xq_ref, xs_ref = oracle.quantize_per_token(x)
+    xq, xs = vq.vq_quantize_per_token(dev(x))
+    assert host(xq)[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 0]  # the hand-worked row itself
+    assert np.array_equal(host(xq), xq_ref)
+    assert np.array_equal(host(xs).view(np.uint32), xs_ref.view(np.uint32))
+    # every fp16 magnitude as the row maximum once: the two divisions must round as the oracle's
+    h = np.arange(1, 0x7C00, 97, dtype=np.uint16).view(np.float16)
+    x = np.zeros((len(h), 16), np.float16)
+    x[:, 3] = h
+    x[:, 5] = (h.astype(np.float32) * np.float32(0.37)).astype(np.float16)
+    x[:, 7] = -(h.astype(np.float32) * np.float32(0.0039)).astype(np.float16)
+    xq_ref, xs_ref = oracle.quantize_per_token(x)
+    xq, xs = vq.vq_quantize_per_token(dev(x))
+    assert np.array_equal(host(xs).view(np.uint32), xs_ref.view(np.uint32))
+    assert np.array_equal(host(xq), xq_ref)
+
+
+def test_quantize_weight_bit_exact(vq, oracle):
+    for (N, K, bits, with_s) in [(48, 320, 8, True), (48, 320, 4, True), (130, 1152, 8, False),
+                                 (130, 1152, 4, False), (3, 2, 4, True), (5, 77, 8, True)]:
+        say(f"quantize_weight N={N} K={K} bits={bits} s={with_s}")
+        g = np.random.default_rng(N * 31 + K + bits)
+        w = g.normal(0, 0.02, (N, K)).astype(np.float32)
+        w[N // 2] = 0
+        s = np.exp(g.uniform(np.log(0.25), np.log(4.0), K)).astype(np.float32) if with_s else None
+        wq_ref, ws_ref = oracle.quantize_weight(w, s, bits)
+        if bits == 4:
+            wq_ref = oracle.pack_int4(wq_ref)
+        wq, ws = vq.vq_quantize_weight(dev(w), None if s is None else dev(s), bits)
+        assert np.array_equal(host(ws).view(np.uint32), ws_ref.view(np.uint32))
+        assert np.array_equal(host(wq), wq_ref)
+
+
+# ---- GEMM + epilogue ---------------------------------------------------------------------
+
+def _gemm_case(vq, oracle, M, N, K, bits, seed, bias=True, full_range=True):
+    g = np.random.default_rng(seed)
+    xq = g.integers(-127, 128, (M, K), dtype=np.int8)
+    qmax = 127 if bits == 8 else 7
+    wq = g.integers(-qmax, qmax + 1, (N, K), dtype=np.int8)
+    xs = np.exp(g.uniform(-8, -2, M)).astype(np.float32)
+    ws = np.exp(g.uniform(-10, -5, N)).astype(np.float32)
+    if M > 3:
+        xs[2] = 0  # a token whose scale is zero -> the row is the bias
+    b = g.normal(0, 0.01, N).astype(np.float16) if bias else None
+    acc_ref = oracle.gemm_i8(xq, wq)
+    y_ref = oracle.dequant(acc_ref, xs, ws, b)
+    if bits == 8:
+        y, acc = vq.vq_gemm_w8a8(dev(xq), dev(xs), dev(wq), dev(ws), None if b is None else dev(b),
+                                 return_acc=True)
+    else:
+        y, acc = vq.vq_gemm_w4a8(dev(xq), dev(xs), dev(oracle.pack_int4(wq)), dev(ws),
+                                 None if b is None else dev(b), return_acc=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(acc), acc_ref), "int32 sums differ"
+    worst = assert_fp16_close(host(y), y_ref, acc_ref, xs, ws, b)
+    return worst, np.array_equal(host(y).view(np.uint16), y_ref.view(np.uint16))
+
+
+GEMM_SHAPES = [(1, 8, 16), (1, 8, 32), (33, 24, 96), (64, 128, 64), (256, 128, 128), (256, 1152, 1152),
+               (300, 136, 224), (257, 264, 160), (513, 260, 64), (17, 7, 32), (240, 2304, 4096),
+               (700, 392, 1184), (31, 129, 4608)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("bits", [8, 4])
+def test_gemm_parity(vq, oracle, M, N, K, bits):
+    if bits == 4 and K % 32:
+        K += 16
+    say(f"gemm w{bits}a8 M={M} N={N} K={K}")
+    worst, exact = _gemm_case(vq, oracle, M, N, K, bits, seed=M * 131 + N * 17 + K + bits)
+    say(f"  max rel err {worst:.2e}, fp16 bit-identical: {exact}")
+
+
+def test_gemm_without_bias_and_saturated_sums(vq, oracle):
+    say("gemm no bias / saturation")
+    _gemm_case(vq, oracle, 70, 40, 256, 8, seed=5, bias=False)
+    _gemm_case(vq, oracle, 70, 40, 256, 4, seed=6, bias=False)
+    K = 4608
+    xq = np.full((40, K), 127, np.int8)
+    wq = np.full((24, K), -127, np.int8)
+    one_m, one_n = np.ones(40, np.float32), np.ones(24, np.float32)
+    y, acc = vq.vq_gemm_w8a8(dev(xq), dev(one_m), dev(wq), dev(one_n), return_acc=True)
+    assert (host(acc) == -74322432).all()          # far beyond 2^24: the sums are integer sums
+    assert np.isinf(host(y).astype(np.float32)).all()  # fp16 overflow goes to infinity, as in the oracle
+    wq4 = np.full((24, K), -7, np.int8)
+    y, acc = vq.vq_gemm_w4a8(dev(xq), dev(one_m), dev(oracle.pack_int4(wq4)), dev(one_n), return_acc=True)
+    assert (host(acc) == -7 * 127 * K).all()
+    # the largest K the library accepts, worst-case operands
+    K = 131072
+    xq = np.full((2, K), -127, np.int8)
+    wq = np.full((8, K), 127, np.int8)
+    y, acc = vq.vq_gemm_w8a8(dev(xq), dev(np.ones(2, np.float32)), dev(wq), dev(np.ones(8, np.float32)),
+                             return_acc=True)
+    assert (host(acc) == -127 * 127 * K).all()
+    wq4 = np.full((8, K), -7, np.int8)
+    y, acc = vq.vq_gemm_w4a8(dev(xq), dev(np.ones(2, np.float32)), dev(oracle.pack_int4(wq4)),
+                             dev(np.ones(8, np.float32)), return_acc=True)
+    assert (host(acc) == 7 * 127 * K).all()
+
+
+def test_identity_weights_select_the_activations(vq):
+    say("gemm identity")
+    g = np.random.default_rng(77)
+    xq = g.integers(-127, 128, (260, 128), dtype=np.int8)
+    eye = np.eye(128, dtype=np.int8)
+    y, acc = vq.vq_gemm_w8a8(dev(xq), dev(np.ones(260, np.float32)), dev(eye), dev(np.ones(128, np.float32)),
+                             return_acc=True)
+    assert np.array_equal(host(acc), xq.astype(np.int32))
+    assert np.array_equal(host(y).astype(np.int32), xq.astype(np.int32))  # |values| < 2048: exact in fp16
+
+
+def test_runs_are_bitwise_repeatable_and_streams_are_honoured(vq, oracle):
+    say("determinism / stream")
+    g = np.random.default_rng(88)
+    x = (g.standard_normal((700, 1152)) * 3).astype(np.float16)
+    w = g.normal(0, 0.02, (392, 1152)).astype(np.float32)
+    wq, ws = oracle.quantize_weight(w, None, 8)
+    b = g.normal(0, 0.01, 392).astype(np.float16)
+    dx, dw, dws, db = dev(x), dev(wq), dev(ws), dev(b)
+    y0 = vq.vq_linear(dx, None, dw, 8, dws, db)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        y1 = vq.vq_linear(dx, None, dw, 8, dws, db)
+    s.synchronize()
+    y2 = vq.vq_linear(dx, None, dw, 8, dws, db, stream=s)
+    s.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(y0, y2)
+    ref = oracle.linear(x, None, wq, 8, ws, b)
+    assert_fp16_close(host(y0), ref["y"], ref["acc"], ref["x_scale"], ws, b)
+
+
+def test_empty_and_rejected_calls_leave_outputs_alone(vq):
+    say("empty / rejected")
+    x = torch.zeros((0, 64), dtype=torch.float16, device="cuda")
+    xq, xs = vq.vq_quantize_per_token(x)
+    assert xq.shape == (0, 64) and xs.shape == (0,)
+    xq = torch.zeros((0, 64), dtype=torch.int8, device="cuda")
+    w = torch.zeros((8, 64), dtype=torch.int8, device="cuda")
+    y = vq.vq_gemm_w8a8(xq, torch.zeros(0, device="cuda"), w, torch.ones(8, device="cuda"))
+    assert y.shape == (0, 8)
+    # K not a multiple of 16 is refused and nothing is written
+    xq = torch.zeros((4, 24), dtype=torch.int8, device="cuda")
+    w = torch.zeros((8, 24), dtype=torch.int8, device="cuda")
+    y = torch.full((4, 8), 7.0, dtype=torch.float16, device="cuda")
+    with pytest.raises(vq.VqError) as e:
+        vq.vq_gemm_w8a8(xq, torch.ones(4, device="cuda"), w, torch.ones(8, device="cuda"), y=y)
+    assert e.value.status == 2
+    torch.cuda.synchronize()
+    assert (y == 7.0).all()
+    # a misaligned view is refused
+    buf = torch.zeros(4 * 64 + 8, dtype=torch.float16, device="cuda")
+    xm = buf[1:1 + 4 * 64].view(4, 64)
+    with pytest.raises(vq.VqError) as e:
+        vq.vq_quantize_per_token(xm)
+    assert e.value.status == 3
+
+
+# ---- the five configurations ----------------------------------------------------------------
+
+def _prepare(oracle, data, bits):
+    wq, ws = oracle.quantize_weight(data.w, data.s, bits)
+    return wq, ws, (wq if bits == 8 else oracle.pack_int4(wq))
+
+
+def _check_layer_rows(vq, oracle, spec, data, rows, what):
+    """Runs the layer on the GPU at full size and compares `rows` (all if None) with the oracle."""
+    bits = spec.w_bits
+    wq, ws, wdev = _prepare(oracle, data, bits)
+    dx = dev(data.x)
+    dcm = None if data.chan_mul is None else dev(data.chan_mul)
+    dw, dws, db = dev(wdev), dev(ws), dev(data.bias)
+    # the offline weight quantizer of the library must give the same weights
+    gwq, gws = vq.vq_quantize_weight(dev(data.w), None if data.s is None else dev(data.s), bits)
+    assert np.array_equal(host(gwq), wdev) and np.array_equal(host(gws).view(np.uint32), ws.view(np.uint32))
+    y = vq.vq_linear(dx, dcm, dw, bits, dws, db)
+    xq, xs = vq.vq_quantize_per_token(dx, dcm)
+    gemm = vq.vq_gemm_w8a8 if bits == 8 else vq.vq_gemm_w4a8
+    y2, acc = gemm(xq, xs, dw, dws, db, return_acc=True)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2), "vq_linear differs from its two halves"
+    sel = np.arange(spec.M) if rows is None else rows
+    ref = oracle.linear(data.x[sel], data.chan_mul, wdev, bits, ws, data.bias)
+    hxq, hxs, hacc, hy = host(xq), host(xs), host(acc), host(y)
+    assert np.array_equal(hxq[sel], ref["xq"]), f"{what}: int8 activations differ"
+    assert np.array_equal(hxs[sel].view(np.uint32), ref["x_scale"].view(np.uint32)), f"{what}: scales differ"
+    assert np.array_equal(hacc[sel], ref["acc"]), f"{what}: int32 sums differ"
+    worst = assert_fp16_close(hy[sel], ref["y"], ref["acc"], ref["x_scale"], ws, data.bias)
+    if rows is not None:
+        # the rows the oracle did not visit: exact integer identity on the whole accumulator
+        assert freivalds_check(hacc, hxq, wq, seed=spec.M + spec.N + spec.K), f"{what}: Freivalds check failed"
+        # and properties that hold at any size
+        assert np.abs(hxq.astype(np.int16)).max() <= 127
+        nz = hxs > 0
+        assert (np.abs(hxq[nz].astype(np.int16)).max(axis=1) == 127).all()
+        assert np.isfinite(hy.astype(np.float32)).all()
+    say(f"  {what}: ok, max rel err {worst:.2e}")
+
+
+def _sample_rows(M, n, seed):
+    g = np.random.default_rng(seed)
+    r = np.unique(np.concatenate([[0, M - 1], g.choice(M, min(n, M), replace=False)]))
+    return r
+
+
+def test_config1_single_w8a8_linear(vq, oracle):
+    from paper_2406_02540_amd import workloads as wl
+    spec = wl.config1()[0]
+    say("config 1")
+    _check_layer_rows(vq, oracle, spec, wl.draw_layer(spec), None, "cfg1")
+
+
+def test_config3_single_w4a8_linear(vq, oracle):
+    from paper_2406_02540_amd import workloads as wl
+    spec = wl.config3()[0]
+    say("config 3")
+    _check_layer_rows(vq, oracle, spec, wl.draw_layer(spec), None, "cfg3")
+
+
+@pytest.mark.parametrize("layer", range(4))
+def test_config2_image_dit_layers(vq, oracle, layer):
+    from paper_2406_02540_amd import workloads as wl
+    spec = wl.config2()[layer]
+    say(f"config 2 {spec.name}")
+    _check_layer_rows(vq, oracle, spec, wl.draw_layer(spec), _sample_rows(spec.M, 384, layer), f"cfg2 {spec.name}")
+
+
+@pytest.mark.parametrize("layer", range(5))
+def test_config4_video_dit_layers(vq, oracle, layer):
+    from paper_2406_02540_amd import workloads as wl
+    spec = wl.config4()[layer]
+    say(f"config 4 {spec.name}")
+    rows = None if spec.M <= 1024 else _sample_rows(spec.M, 256, 40 + layer)
+    _check_layer_rows(vq, oracle, spec, wl.draw_layer(spec), rows, f"cfg4 {spec.name}")
+
+
+_CFG5_BASE = {}
+
+
+def _cfg5_base(wl, M, K):
+    """One base activation per input shape of the sweep (drawn once per test session)."""
+    key = (M, K)
+    if key not in _CFG5_BASE:
+        ident = {(wl.VIDEO_TOKENS, wl.HIDDEN): 0, (wl.VIDEO_TOKENS, wl.MLP): 1,
+                 (wl.TEXT_TOKENS, wl.TEXT_DIM): 2}[key]
+        _CFG5_BASE[key] = wl.draw_x(wl.LayerSpec("x", M, K, 0, 8, cfg=5, block=0, layer=ident, x_kind="video"))
+    return _CFG5_BASE[key]
+
+
+@pytest.mark.parametrize("t,block", [(1, 0), (1, 27), (10, 0), (20, 0)])
+def test_config5_mixed_precision_sweep_sampled(vq, oracle, t, block):
+    """Blocks 0 and 27 of the 28-block sweep at denoising steps 1, 10 and 20, sampled rows."""
+    from paper_2406_02540_amd import workloads as wl
+    specs = wl.config5()
+    assert wl.config5_plan().shape == (168,)
+    assert {s.w_bits for s in specs if s.block in (0, 27)} == {8, 4}  # both precisions are exercised
+    for spec in [s for s in specs if s.block == block]:
+        w, bias, s, cm = wl.draw_weights(spec)
+        x0 = _cfg5_base(wl, spec.M, spec.K)
+        x = (x0.astype(np.float32) * np.float32(wl.config5_step_scale(t))).astype(np.float16)
+        data = wl.LayerData(spec, x, w, bias, s, cm)
+        say(f"config 5 step {t} block {block} {spec.name} w{spec.w_bits}")
+        rows = None if spec.M <= 1024 else _sample_rows(spec.M, 64, t * 100 + spec.layer)
+        _check_layer_rows(vq, oracle, spec, data, rows, f"cfg5 t={t} b={block} {spec.name}")

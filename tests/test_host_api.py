@@ -1,0 +1,147 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol include/vq.h declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "vq.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2406_02540_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2406_02540_amd import build
+        build.build(verbose=False)
+    return binding.lib()
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_entry_points():
+    names = _declared()
+    for n in ("vq_quantize_per_token", "vq_gemm_w8a8", "vq_gemm_w4a8", "vq_linear",
+              "vq_linear_workspace_bytes", "vq_quantize_weight", "vq_status_string"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2406_02540_amd import binding
+    for n in _declared():
+        assert hasattr(lib, n), n
+        assert n in binding.SIGNATURES, f"binding has no signature for {n}"
+    assert sorted(binding.SIGNATURES) == _declared()
+
+
+def test_binding_exposes_the_same_names():
+    import paper_2406_02540_amd as pkg
+    for n in _declared():
+        if n == "vq_status_string":
+            continue
+        assert callable(getattr(pkg, n)), n
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(8):
+        s = lib.vq_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert lib.vq_status_string(99).decode() == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    f = lib.vq_linear_workspace_bytes
+    assert f(32768, 4608, 1152, 8) == 32768 * 1152 + 4 * 32768
+    assert f(240, 2304, 4096, 4) == 240 * 4096 + 4 * 240
+    assert f(3, 8, 16, 8) == 48 + 16          # both parts rounded up to 16 bytes
+    assert f(0, 8, 16, 8) == 0
+    assert f(-1, 8, 16, 8) == 0 and f(1, 8, 0, 8) == 0 and f(1, 8, 16, 5) == 0
+
+
+A = 0x10000  # a made-up, 16-byte aligned, non-NULL address; never dereferenced by validation
+P = ctypes.c_void_p
+
+
+def test_quantize_argument_errors(lib):
+    q = lib.vq_quantize_per_token
+    assert q(P(A), None, P(A), P(A), -1, 64, None) == 2
+    assert q(P(A), None, P(A), P(A), 4, 0, None) == 2
+    assert q(P(A), None, P(A), P(A), 4, 131073, None) == 2
+    assert q(None, None, P(A), P(A), 4, 64, None) == 1
+    assert q(P(A), None, None, P(A), 4, 64, None) == 1
+    assert q(P(A), None, P(A), None, 4, 64, None) == 1
+    assert q(P(A + 2), None, P(A), P(A), 4, 64, None) == 3
+    assert q(P(A), P(A + 4), P(A), P(A), 4, 64, None) == 3
+    assert q(None, None, None, None, 0, 64, None) == 0  # empty: nothing to do
+
+
+def test_gemm_argument_errors(lib):
+    for g, kmult in ((lib.vq_gemm_w8a8, 16), (lib.vq_gemm_w4a8, 32)):
+        ok = [P(A), P(A), P(A), P(A), None, P(A), None]
+        assert g(*ok, 4, 8, kmult - 8, None) == 2      # K not a multiple of what the path needs
+        assert g(*ok, 4, 8, 0, None) == 2
+        assert g(*ok, 4, -8, kmult, None) == 2
+        assert g(*ok, 4, 8, 131072 + kmult, None) == 2  # beyond the int32-safe K
+        for i in (0, 1, 2, 3, 5):
+            bad = list(ok)
+            bad[i] = None
+            assert g(*bad, 4, 8, kmult, None) == 1
+            bad[i] = P(A + 8)
+            assert g(*bad, 4, 8, kmult, None) == 3
+        bad = list(ok)
+        bad[4] = P(A + 2)
+        assert g(*bad, 4, 8, kmult, None) == 3
+        assert g(None, None, None, None, None, None, None, 0, 8, kmult, None) == 0
+        assert g(None, None, None, None, None, None, None, 4, 0, kmult, None) == 0
+
+
+def test_linear_argument_errors(lib):
+    f = lib.vq_linear
+    need = lib.vq_linear_workspace_bytes(4, 8, 64, 8)
+    base = dict(x=P(A), cm=None, w=P(A), bits=8, ws=P(A), b=None, y=P(A), wk=P(A), wb=need, M=4, N=8, K=64)
+
+    def call(**kw):
+        a = dict(base, **kw)
+        return f(a["x"], a["cm"], a["w"], a["bits"], a["ws"], a["b"], a["y"], a["wk"], a["wb"],
+                 a["M"], a["N"], a["K"], None)
+
+    assert call(bits=5) == 7
+    assert call(K=24) == 2
+    assert call(bits=4, K=48) == 2
+    assert call(wk=None) == 1
+    assert call(wk=P(A + 4)) == 3
+    assert call(wb=need - 1) == 4
+    assert call(x=None) == 1 and call(w=None) == 1 and call(ws=None) == 1 and call(y=None) == 1
+    assert call(M=0) == 0
+
+
+def test_quantize_weight_argument_errors(lib):
+    f = lib.vq_quantize_weight
+    assert f(P(A), None, 3, P(A), P(A), 4, 64, None) == 7
+    assert f(P(A), None, 4, P(A), P(A), 4, 63, None) == 2
+    assert f(None, None, 8, P(A), P(A), 4, 64, None) == 1
+    assert f(P(A), P(A + 4), 8, P(A), P(A), 4, 64, None) == 3
+    assert f(None, None, 8, None, None, 0, 64, None) == 0
+
+
+def test_no_gfx950_device_is_an_error_not_a_launch(lib):
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present; made-up pointers must not reach a kernel")
+    assert lib.vq_quantize_per_token(P(A), None, P(A), P(A), 4, 64, None) == 6
+    assert lib.vq_gemm_w8a8(P(A), P(A), P(A), P(A), None, P(A), None, 4, 8, 64, None) == 6
+
+
+def test_binding_refuses_host_tensors():
+    torch = pytest.importorskip("torch")
+    import paper_2406_02540_amd as pkg
+    with pytest.raises(TypeError):
+        pkg.vq_quantize_per_token(torch.zeros((2, 8), dtype=torch.float16))
