@@ -4,25 +4,34 @@
 // implementation of quantized linear layers"; Sec. 4.1 for the grouping):
 //     acc[m,n] = sum_k xq[m,k] * wq[n,k]
 //     y[m,n]   = fp16(float(acc) * x_scale[m] * w_scale[n] + bias[n])
-// W4A8 (appendix "Performance under lower bitwidth"): 4-bit weights are widened
-// to int8 on their way into LDS and then take the same mainloop.
+// W4A8 (appendix "Performance under lower bitwidth"): 4-bit weights are staged
+// in LDS packed and widened to int8 on their way from LDS into the MFMA operand
+// registers; the mainloop is otherwise the same.
 //
 // Shape of the kernel
-//   - workgroup tile: 256 tokens x 128 output channels, 4 wavefronts (2 x 2),
+//   - workgroup tile: 256 tokens x 256 output channels, 8 wavefronts (2 x 4),
 //     each wavefront 128 tokens x 64 channels = 2 x 4 MFMA 32x32x32 blocks,
-//     128 int32 accumulators per lane; two workgroups per CU so that one
-//     group's epilogue and LDS traffic overlap the other's MFMAs.
-//   - K is walked in stages of 64 bytes, double buffered in LDS.  Activations
-//     (and int8 weights) go global -> LDS directly (buffer_load ... lds, 16 B
-//     per lane); 4-bit weights go through registers, are widened there and
-//     written to LDS as int8.
-//   - LDS tiles are [row][64 B] with the four 16-byte chunks of a row XOR-ed
-//     by (row/4)%4, which makes the 16-lane groups of a ds_read_b128 hit 16
+//     128 int32 accumulators per lane, two wavefronts per SIMD.  The tile is
+//     large because the L2 -> CU path, not HBM, is what the operand traffic
+//     loads: bytes per multiply-add fall with the tile edge.
+//   - K is walked in stages of 128 bytes, double buffered in LDS.  A stage
+//     takes one full 128-byte cache line per row, so every L2 request is a
+//     whole line.  Activations and weights go global -> LDS directly
+//     (buffer_load ... lds, 16 B per lane, no registers in between); the loads
+//     of stage i+1 are in flight while stage i is multiplied.  4-bit weights
+//     travel packed (half the bytes).
+//   - The direct loads are issued from inline assembly and waited for with an
+//     explicit s_waitcnt: the compiler would otherwise wait for all of them
+//     before every LDS read and undo the prefetch.
+//   - LDS tiles are [row][128 B] with the eight 16-byte chunks of a row XOR-ed
+//     by (row/2)%8, which makes the 16-lane groups of a ds_read_b128 hit 16
 //     different bank groups.
 //   - The weights are the MFMA row operand and the tokens the column operand,
 //     so a lane owns one token and, by permuting which weight row sits in
-//     which MFMA row, 32 consecutive output channels of it: the epilogue
-//     writes 16-byte pieces of a row of Y without a transpose.
+//     which MFMA row, 32 consecutive output channels of it.  The epilogue
+//     scales and narrows in registers, turns each wavefront's 128 x 64 block
+//     through LDS and writes whole 128-byte lines of Y, bypassing the caches'
+//     retention (nontemporal): the operands keep the L2.
 //   - Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the
 //     id is remapped so that each XCD works on a contiguous run of tiles,
 //     ordered in bands of 8 token tiles, and its L2 sees each panel once.
@@ -38,6 +47,7 @@
 namespace vq {
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -45,15 +55,20 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
 constexpr int kTileT = 256;                 // tokens per workgroup
-constexpr int kTileC = 128;                 // output channels per workgroup
-constexpr int kTileK = 64;                  // K bytes per stage
-constexpr int kThreads = 256;
-constexpr int kXStage = kTileT * kTileK;    // 16 KiB
-constexpr int kWStage = kTileC * kTileK;    // 8 KiB
-constexpr int kLdsBytes = 2 * (kXStage + kWStage);
+constexpr int kTileC = 256;                 // output channels per workgroup
+constexpr int kTileK = 128;                 // K bytes per stage (one cache line per row)
+constexpr int kThreads = 512;               // 8 wavefronts
+constexpr int kWaves = kThreads / 64;
+constexpr int kXStage = kTileT * kTileK;    // 32 KiB
+constexpr int kWStage = kTileC * kTileK;    // 32 KiB (16 KiB used by packed 4-bit weights)
+constexpr int kStages = 2;
+constexpr int kLdsBytes = kStages * (kXStage + kWStage);  // 128 KiB
+constexpr int kEpiRow = 128 + 16;           // bytes per token row of the epilogue staging (padded)
+constexpr int kEpiWave = 64 * kEpiRow;      // one wavefront stages 64 tokens x 64 channels at a time
 constexpr int kBand = 8;                    // token tiles per band in the tile order
 constexpr int kXcds = 8;
 constexpr unsigned kRsrcFlags = 0x00020000; // raw buffer, 32-bit data format
+static_assert(kWaves * kEpiWave <= kLdsBytes, "epilogue staging must fit the stage buffers");
 
 struct GemmArgs {
     const int8_t* xq;
@@ -66,11 +81,6 @@ struct GemmArgs {
     int M, N, K;
     int tiles_t, tiles_c, tiles, tiles_per_xcd;
 };
-
-// Byte offset of 16-byte chunk `chunk` of `row` in a swizzled [rows][64] tile.
-__device__ __forceinline__ int swz(int row, int chunk) {
-    return row * kTileK + ((chunk ^ ((row >> 2) & 3)) << 4);
-}
 
 // LDS row r of the weight tile holds which output channel of the tile.
 // Rows are kept in MFMA order: r = slab*64 + b*32 + rho with rho = 8j + 4h + i
@@ -87,12 +97,62 @@ __device__ __forceinline__ unsigned clamp_u32(long v) {
     return v > 0xFFFFFFFFl ? 0xFFFFFFFFu : (unsigned)v;
 }
 
-template <int W_BITS>
+// Raw buffer descriptor: base address, no stride, size in bytes (accesses past
+// it read as zero and never fault), 32-bit data format.
+__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
+    const unsigned long long p = (unsigned long long)base;
+    v4i r;
+    r[0] = (int)(unsigned)p;
+    r[1] = (int)(unsigned)(p >> 32) & 0xFFFF;
+    r[2] = (int)bytes;
+    r[3] = (int)kRsrcFlags;
+    return r;
+}
+
+// 16 bytes per lane from buffer offset voff + soff straight into LDS at
+// lds_addr + 16 * lane (lds_addr is wave-uniform and goes through M0).  Counts
+// in vmcnt; the compiler does not know about it, see wait_loads_and_barrier().
+__device__ __forceinline__ void load_to_lds_16(v4i rsrc, unsigned lds_addr, int voff, int soff) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "buffer_load_dwordx4 %1, %2, %3 offen lds"
+        :
+        : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+        : "memory");
+}
+
+// Waits until all of this wave's direct loads have landed and all its LDS
+// accesses are done, then joins the workgroup barrier.
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" : : : "memory");
+}
+
+// 16 nibbles (two dwords) -> 16 bytes holding 16 * w: the nibble is moved to
+// the high half of its byte, sign bit included, in the order of K.
+__device__ __forceinline__ v4i widen_nibbles(v2i p) {
+    v4i o;
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+        const unsigned w = (unsigned)p[d];
+        const unsigned even = (w << 4) & 0xF0F0F0F0u;  // k = 0,2,4,6 of this dword
+        const unsigned odd = w & 0xF0F0F0F0u;          // k = 1,3,5,7
+        o[2 * d] = (int)__builtin_amdgcn_perm(odd, even, 0x05010400u);      // k = 0,1,2,3
+        o[2 * d + 1] = (int)__builtin_amdgcn_perm(odd, even, 0x07030602u);  // k = 4,5,6,7
+    }
+    return o;
+}
+
+// K_TAIL: K is a multiple of 16 but not of 128 (the last stage is partly past K).
+template <int W_BITS, bool K_TAIL>
 __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a) {
     __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes];
-    // layout: [X stage 0][X stage 1][W stage 0][W stage 1]
+    // layout: [X stage 0][X stage 1][W stage 0][W stage 1]; a W stage is
+    // [256 rows][128 B] of int8 or, for 4-bit weights, [256 rows][64 B] of nibbles.
     int8_t* const lds_x = lds;
-    int8_t* const lds_w = lds + 2 * kXStage;
+    int8_t* const lds_w = lds + kStages * kXStage;
+    const unsigned lds_x_addr = (unsigned)(uintptr_t)(lds_ptr)lds_x;
+    const unsigned lds_w_addr = (unsigned)(uintptr_t)(lds_ptr)lds_w;
 
     // ---- which tile ------------------------------------------------------
     const int pid = blockIdx.x;
@@ -111,102 +171,78 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Waves w and w+4 share a SIMD: they get the same token half and channel
+    // slabs two apart, so a tile that is only half full of channels still
+    // leaves one working wave on every SIMD.
     const int wave_t = wave & 1;   // which 128 tokens
     const int wave_c = wave >> 1;  // which 64 channels
 
     const int K = a.K;
     const int rows_x = (int)min((long)kTileT, a.M - tok0);
     const int rows_w = (int)min((long)kTileC, a.N - ch0);
+    // a wave whose 64 channels (or 128 tokens) lie wholly past the matrix has nothing to multiply
+    const bool wave_live = (wave_c * 64 < rows_w) && (wave_t * 128 < rows_x);
 
-    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(a.xq + tok0 * K), 0, clamp_u32((a.M - tok0) * (long)K), kRsrcFlags);
-    constexpr int kWDiv = (W_BITS == 8) ? 1 : 2;  // bytes of K per stored byte
-    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)((const int8_t*)a.w + ch0 * (K / kWDiv)), 0,
-        clamp_u32((a.N - ch0) * (long)(K / kWDiv)), kRsrcFlags);
+    constexpr int kWDiv = (W_BITS == 8) ? 1 : 2;  // values of K per stored byte
+    const v4i rsrc_x = make_rsrc(a.xq + tok0 * K, clamp_u32((a.M - tok0) * (long)K));
+    const v4i rsrc_w = make_rsrc((const int8_t*)a.w + ch0 * (K / kWDiv),
+                                 clamp_u32((a.N - ch0) * (long)(K / kWDiv)));
 
     // ---- global -> LDS mapping ---------------------------------------------
-    // One direct load fills 1 KiB = 16 rows x 64 B; lane l writes bytes
-    // [16 l, 16 l + 16), i.e. row l/4, physical chunk l%4, which under the
-    // swizzle is logical chunk (l%4) ^ (l/16).
-    const int ld_row = lane >> 2;
-    const int ld_chunk = (lane & 3) ^ (lane >> 4);
-    int voff_x[4];  // wave w loads X row groups w, w+4, w+8, w+12 (16 groups)
+    // One direct load fills 1 KiB; lane l writes bytes [16 l, 16 l + 16).
+    // int8 tiles: 8 rows x 128 B per load, lane l = row l/8, physical chunk l%8,
+    // which under the swizzle holds logical chunk (l%8) ^ ((row/2)%8).  Wave w
+    // loads row groups w, w+8, w+16, w+24 of each tile, so row/2 mod 8 is
+    // (4 (w%2) + l/16) % 8 for all of them.
+    const int ld_row = lane >> 3;
+    const int ld_chunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
+    int voff_x[4], voff_w[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int r = min((wave + 4 * j) * 16 + ld_row, rows_x - 1);
-        voff_x[j] = r * K + ld_chunk * 16;
+        const int r = (wave + 8 * j) * 8 + ld_row;
+        voff_x[j] = min(r, rows_x - 1) * K + ld_chunk * 16;
+        voff_w[j] = min(w_row_to_channel(r), rows_w - 1) * K + ld_chunk * 16;
     }
-    int voff_w[2];  // W8: wave w loads W row groups w, w+4 (8 groups)
-    if (W_BITS == 8) {
+    if (W_BITS == 4) {
+        // packed tile [256 rows][64 B]: 16 rows x 64 B per load, lane l = row l/4,
+        // physical chunk l%4 holding logical chunk (l%4) ^ ((row/4)%4) = (l%4) ^ (l/16).
+        // Wave w loads row groups w and w+8.
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int r = (wave + 4 * j) * 16 + ld_row;
-            const int c = min(w_row_to_channel(r), rows_w - 1);
-            voff_w[j] = c * K + ld_chunk * 16;
+            const int r = (wave + 8 * j) * 16 + (lane >> 2);
+            voff_w[j] = min(w_row_to_channel(r), rows_w - 1) * (K / 2) + (((lane & 3) ^ (lane >> 4)) << 4);
         }
-    }
-    // W4: thread t brings 32 nibbles (16 B) of LDS row t/2, K-half t%2.
-    const int w4_row = tid >> 1, w4_half = tid & 1;
-    int voff_w4 = 0;
-    if (W_BITS == 4) {
-        const int c = min(w_row_to_channel(w4_row), rows_w - 1);
-        voff_w4 = c * (K / 2) + w4_half * 16;
     }
 
-    auto issue_x_and_w8 = [&](int stage, int k0) {
+    auto issue_stage = [&](int st, int k0) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rsrc_x, (lds_ptr)(lds_x + stage * kXStage + (wave + 4 * j) * 1024), 16, voff_x[j],
-                k0, 0, 0);
+            load_to_lds_16(rsrc_x, lds_x_addr + st * kXStage + (wave + 8 * j) * 1024, voff_x[j], k0);
         if (W_BITS == 8) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rsrc_w, (lds_ptr)(lds_w + stage * kWStage + (wave + 4 * j) * 1024), 16,
-                    voff_w[j], k0, 0, 0);
-        }
-    };
-    auto load_w4 = [&](int k0) -> v4i {
-        return __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, voff_w4, k0 / 2, 0);
-    };
-    // Widen 32 nibbles to 32 bytes holding 16 * w (nibble moved to the high
-    // half of its byte, sign bit included) and store them as chunks 2*half and
-    // 2*half + 1 of the row.
-    auto store_w4 = [&](int stage, v4i p) {
-        v4i lo, hi;
+            for (int j = 0; j < 4; ++j)
+                load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0);
+        } else {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const unsigned w = (unsigned)p[d];
-            const unsigned even = (w << 4) & 0xF0F0F0F0u;  // k = 0,2,4,6 of this dword
-            const unsigned odd = w & 0xF0F0F0F0u;          // k = 1,3,5,7
-            const unsigned k0123 = __builtin_amdgcn_perm(odd, even, 0x05010400u);
-            const unsigned k4567 = __builtin_amdgcn_perm(odd, even, 0x07030602u);
-            if (d < 2) {
-                lo[2 * d] = (int)k0123;
-                lo[2 * d + 1] = (int)k4567;
-            } else {
-                hi[2 * (d - 2)] = (int)k0123;
-                hi[2 * (d - 2) + 1] = (int)k4567;
-            }
+            for (int j = 0; j < 2; ++j)
+                load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0 / 2);
         }
-        int8_t* base = lds_w + stage * kWStage;
-        *(v4i*)(base + swz(w4_row, 2 * w4_half)) = lo;
-        *(v4i*)(base + swz(w4_row, 2 * w4_half + 1)) = hi;
     };
 
     // ---- LDS -> MFMA operand mapping -----------------------------------------
     // Operand rows of a 32x32x32 block: lane l supplies row l%32, 16 bytes of K
-    // chosen by l/32; a stage holds two such K steps (chunks 0,1 and 2,3).
+    // chosen by l/32; a stage holds four such K steps (chunks 2ks and 2ks+1).
     const int fr_row = lane & 31;
-    const int fr_sw = (fr_row >> 2) & 3;
-    int x_off[2], w_off[2];
+    int x_off[4], w_off[4];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const int phys = ((2 * ks + (lane >> 5)) ^ fr_sw) << 4;
+    for (int ks = 0; ks < 4; ++ks) {
+        const int phys = ((2 * ks + (lane >> 5)) ^ ((fr_row >> 1) & 7)) << 4;
         x_off[ks] = (wave_t * 128 + fr_row) * kTileK + phys;
-        w_off[ks] = (wave_c * 64 + fr_row) * kTileK + phys;
+        if (W_BITS == 8)
+            w_off[ks] = (wave_c * 64 + fr_row) * kTileK + phys;
+        else  // 8 bytes of nibbles: 16-byte chunk ks (swizzled by (row/4)%4), half l/32
+            w_off[ks] = (wave_c * 64 + fr_row) * (kTileK / 2) + ((ks ^ ((fr_row >> 2) & 3)) << 4) +
+                        (lane >> 5) * 8;
     }
 
     v16i acc[2][4];
@@ -218,65 +254,54 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             for (int r = 0; r < 16; ++r) acc[cb][tb][r] = 0;
 
     const int nk = (K + kTileK - 1) / kTileK;
-    const bool k_tail = (K % kTileK) != 0;
 
-    // prologue: stage 0
-    issue_x_and_w8(0, 0);
-    if (W_BITS == 4) store_w4(0, load_w4(0));
-
+    issue_stage(0, 0);
     for (int it = 0; it < nk; ++it) {
-        const int stage = it & 1;
-        __syncthreads();  // stage `it` has landed for every wave; stage it-1 is no longer read
+        const int st = it & 1;
+        // Stage `it` has landed for every wave, and every wave is done reading
+        // stage it-1, whose buffer the loads issued next overwrite.
+        wait_loads_and_barrier();
+        if (it + 1 < nk) issue_stage(st ^ 1, (it + 1) * kTileK);
+        if (!wave_live) continue;
 
-        v4i xf[2][4], wf[2][2];
-        const int8_t* xs = lds_x + stage * kXStage;
-        const int8_t* ws = lds_w + stage * kWStage;
+        const int8_t* xs = lds_x + st * kXStage;
+        const int8_t* ws = lds_w + st * kWStage;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < 4; ++ks) {
+            v4i xf[4], wf[2];
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-                wf[ks][cb] = *(const v4i*)(ws + w_off[ks] + cb * 32 * kTileK);
+            for (int cb = 0; cb < 2; ++cb) {
+                if (W_BITS == 8)
+                    wf[cb] = *(const v4i*)(ws + w_off[ks] + cb * 32 * kTileK);
+                else
+                    wf[cb] = widen_nibbles(*(const v2i*)(ws + w_off[ks] + cb * 32 * (kTileK / 2)));
+            }
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb)
-                xf[ks][tb] = *(const v4i*)(xs + x_off[ks] + tb * 32 * kTileK);
-        }
-        if (k_tail && it == nk - 1) {
-            // K is a multiple of 16 but not of 64: chunks past K hold bytes of
-            // the next row (or nothing); a zero weight operand removes them.
+            for (int tb = 0; tb < 4; ++tb) xf[tb] = *(const v4i*)(xs + x_off[ks] + tb * 32 * kTileK);
+            if (K_TAIL && it == nk - 1) {
+                // K is a multiple of 16 but not of 128: chunks past K hold bytes of the
+                // next row (or nothing); a zero weight operand removes them.
+                if (it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K) {
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const bool valid = it * kTileK + (2 * ks + (lane >> 5)) * 16 < K;
-                if (!valid) {
-#pragma unroll
-                    for (int cb = 0; cb < 2; ++cb) wf[ks][cb] = v4i{0, 0, 0, 0};
+                    for (int cb = 0; cb < 2; ++cb) wf[cb] = v4i{0, 0, 0, 0};
                 }
             }
-        }
-
-        v4i w4_next;
-        const bool more = it + 1 < nk;
-        if (more) {
-            issue_x_and_w8(stage ^ 1, (it + 1) * kTileK);
-            if (W_BITS == 4) w4_next = load_w4((it + 1) * kTileK);
-        }
-
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
                 for (int tb = 0; tb < 4; ++tb)
-                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks][cb], xf[ks][tb],
-                                                                        acc[cb][tb], 0, 0, 0);
-
-        if (W_BITS == 4 && more) store_w4(stage ^ 1, w4_next);
+                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[cb], xf[tb], acc[cb][tb], 0, 0, 0);
+        }
     }
 
     // ---- epilogue ------------------------------------------------------------
     // Lane (h = lane/32, t = lane%32) holds, for each of its 4 token blocks, the
     // 32 channels chl .. chl+31: accumulator block b, register r <-> chl + 16 b + r.
+    wait_loads_and_barrier();  // the stage buffers are free: they become the staging area
+    if (!wave_live) return;
     const int h = lane >> 5;
-    const long ch = ch0 + wave_c * 64 + 32 * h;
+    const long chw = ch0 + wave_c * 64;  // first channel of this wave
+    const long ch = chw + 32 * h;        // first channel of this lane
     const bool vec = (a.N % 8) == 0;
     // the 4-bit path accumulated 16 * w: fold the exact 1/16 into the channel scale
     const float wmul = (W_BITS == 4) ? 0.0625f : 1.0f;
@@ -315,11 +340,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         }
     }
 
+    int8_t* const stage = lds + wave * kEpiWave;  // this wave's 64 tokens x (128 + 16) bytes
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
         const long tok = tok0 + wave_t * 128 + tb * 32 + (lane & 31);
-        if (tok >= a.M) continue;
-        const float xsc = a.x_scale[tok];
+        const bool tok_ok = tok < a.M;
+        const float xsc = tok_ok ? a.x_scale[tok] : 0.0f;
         _Float16* yrow = a.y + tok * a.N + ch;
         int32_t* arow = a.acc_out ? a.acc_out + tok * a.N + ch : nullptr;
 #pragma unroll
@@ -337,14 +363,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                 out[e] = (_Float16)f;
             }
             if (vec) {
-                if (ch + 8 * g < a.N) {
-                    *(half8*)(yrow + 8 * g) = out;
-                    if (arow) {
-                        *(v4i*)(arow + 8 * g) = v4i{iv[0], iv[1], iv[2], iv[3]};
-                        *(v4i*)(arow + 8 * g + 4) = v4i{iv[4], iv[5], iv[6], iv[7]};
-                    }
+                // staged: token row (tb%2)*32 + t, byte column 64 h + 16 g
+                *(half8*)(stage + ((tb & 1) * 32 + (lane & 31)) * kEpiRow + 64 * h + 16 * g) = out;
+                if (arow && tok_ok && ch + 8 * g < a.N) {
+                    *(v4i*)(arow + 8 * g) = v4i{iv[0], iv[1], iv[2], iv[3]};
+                    *(v4i*)(arow + 8 * g + 4) = v4i{iv[4], iv[5], iv[6], iv[7]};
                 }
-            } else {
+            } else if (tok_ok) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     if (ch + 8 * g + e < a.N) {
@@ -353,6 +378,23 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                     }
                 }
             }
+        }
+        if (vec && (tb & 1)) {
+            // 64 token rows x 128 B are staged: write them out a full line per 8 lanes.
+            // Only this wave touches its staging area; LDS operations of a wave execute
+            // in order, the fence only keeps the compiler from reordering them.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = i * 8 + (lane >> 3);
+                const half8 v = *(const half8*)(stage + row * kEpiRow + (lane & 7) * 16);
+                const long t = tok0 + wave_t * 128 + (tb - 1) * 32 + row;
+                const long c = chw + (lane & 7) * 8;
+                if (t < a.M && c < a.N) __builtin_nontemporal_store(v, (half8*)(a.y + t * a.N + c));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
@@ -380,10 +422,14 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     a.tiles = (int)tiles;
     a.tiles_per_xcd = (a.tiles + kXcds - 1) / kXcds;
     const dim3 grid((unsigned)(a.tiles_per_xcd * kXcds)), block(kThreads);
-    if (w_bits == 8)
-        hipLaunchKernelGGL((gemm_i8_dequant<8>), grid, block, 0, stream, a);
-    else
-        hipLaunchKernelGGL((gemm_i8_dequant<4>), grid, block, 0, stream, a);
+    const bool tail = (K % kTileK) != 0;
+    if (w_bits == 8) {
+        if (tail) hipLaunchKernelGGL((gemm_i8_dequant<8, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((gemm_i8_dequant<8, false>), grid, block, 0, stream, a);
+    } else {
+        if (tail) hipLaunchKernelGGL((gemm_i8_dequant<4, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((gemm_i8_dequant<4, false>), grid, block, 0, stream, a);
+    }
     return hipGetLastError();
 }
 
