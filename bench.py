@@ -37,8 +37,11 @@ def parse():
     p.add_argument("--warmup", type=int, default=3)
     p.add_argument("--workload", default="video", choices=["video", "image", "video-w4"])
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--cpu-rows", type=int, default=4096,
-                   help="tokens per layer the CPU oracle is timed on")
+    p.add_argument("--cpu-seconds", type=float, default=15.0,
+                   help="about how long the CPU oracle leg may run (it picks its token sample to fit)")
+    p.add_argument("--copy-calibration", action="store_true",
+                   help="only run a plain 1 GiB device copy a few times (reference for the "
+                        "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     return p.parse_args()
 
 
@@ -78,6 +81,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones((1 << 30,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}))
+        return
     specs, workload_name = layer_specs(args.workload)
 
     # ---- inputs: drawn on the host from the seeded recipe, then resident in HBM ----------------
@@ -175,19 +186,28 @@ def main():
         prep = []
         for L in layers:
             s, d = L["spec"], L["data"]
-            rows = min(s.M, args.cpu_rows)
             wq, ws = oracle.quantize_weight(d.w, d.s, s.w_bits)
-            prep.append((s, d, rows, wq if s.w_bits == 8 else oracle.pack_int4(wq), ws))
-        t0 = time.perf_counter()
-        ops = 0
-        for s, d, rows, wdev, ws in prep:
-            oracle.linear(d.x[:rows], d.chan_mul, wdev, s.w_bits, ws, d.bias)
-            ops += 2 * rows * s.N * s.K
-        dt = time.perf_counter() - t0
+            prep.append((s, d, wq if s.w_bits == 8 else oracle.pack_int4(wq), ws))
+
+        def run_rows(rows_big):
+            t0 = time.perf_counter()
+            ops = 0
+            for s, d, wdev, ws in prep:
+                rows = min(s.M, rows_big)
+                oracle.linear(d.x[:rows], d.chan_mul, wdev, s.w_bits, ws, d.bias)
+                ops += 2 * rows * s.N * s.K
+            return ops, time.perf_counter() - t0
+
+        ops, dt = run_rows(256)                      # short probe to size the sample
+        rate = ops / dt
+        big_ops_per_row = sum(2 * s.N * s.K for s, _, _, _ in prep if s.M > 256)
+        rows_big = int(max(256, min(max(s.M for s, _, _, _ in prep), args.cpu_seconds * rate / big_ops_per_row)))
+        rows_big = max(256, rows_big // 256 * 256)
+        ops, dt = run_rows(rows_big)
         cpu = dict(value=round(ops / dt / 1e12, 6), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
-                   sample="first %d tokens of every layer (all %s of the small ones), whole layer "
-                          "(quantize + integer GEMM + dequantize), %.1f s" % (args.cpu_rows, "tokens", dt))
-        log(f"cpu oracle: {ops / dt / 1e9:.1f} GOP/s on {cpu['cores']} threads ({dt:.1f} s)")
+                   sample="first %d tokens of every layer (all tokens of layers with fewer), whole layer "
+                          "(quantize + integer GEMM + dequantize), %.1f s" % (rows_big, dt))
+        log(f"cpu oracle: {ops / dt / 1e9:.1f} GOP/s on {cpu['cores']} threads ({dt:.1f} s, {rows_big} tokens/layer)")
 
     out = {
         "metric": "quantized-linear int8 TOPS (quant+GEMM+dequant)",
