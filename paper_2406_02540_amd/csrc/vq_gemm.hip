@@ -40,8 +40,9 @@
 // same whatever the tiling; the 4-bit path multiplies by 16 * w (nibble left in
 // the high half of the byte) and divides the sum by 16 exactly afterwards.
 //
-// Compiled with -ffp-contract=off: the epilogue is two fp32 multiplies and one
-// add, each rounded on its own, then a round-to-nearest-even narrowing.
+// The epilogue computes fp16(fma(float(acc) * x_scale, w_scale, bias)) in fp32: one
+// rounding fewer than the three separate operations, so an output can differ from
+// the separately rounded value in the last fp16 place.
 #include "vq_internal.h"
 
 namespace vq {
@@ -63,6 +64,7 @@ constexpr int kXStage = kTileT * kTileK;    // 32 KiB
 constexpr int kWStage = kTileC * kTileK;    // 32 KiB (16 KiB used by packed 4-bit weights)
 constexpr int kStages = 2;
 constexpr int kLdsBytes = kStages * (kXStage + kWStage);  // 128 KiB
+constexpr int kScaleBytes = 3 * 1024;       // w_scale[256] fp32 | bias[256] fp16 (+pad) | x_scale[256] fp32
 constexpr int kEpiRow = 128 + 16;           // bytes per token row of the epilogue staging (padded)
 constexpr int kEpiWave = 64 * kEpiRow;      // one wavefront stages 64 tokens x 64 channels at a time
 constexpr int kBand = 8;                    // token tiles per band in the tile order
@@ -146,13 +148,15 @@ __device__ __forceinline__ v4i widen_nibbles(v2i p) {
 // K_TAIL: K is a multiple of 16 but not of 128 (the last stage is partly past K).
 template <int W_BITS, bool K_TAIL>
 __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a) {
-    __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes];
+    __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes + kScaleBytes];
     // layout: [X stage 0][X stage 1][W stage 0][W stage 1]; a W stage is
     // [256 rows][128 B] of int8 or, for 4-bit weights, [256 rows][64 B] of nibbles.
     int8_t* const lds_x = lds;
     int8_t* const lds_w = lds + kStages * kXStage;
     const unsigned lds_x_addr = (unsigned)(uintptr_t)(lds_ptr)lds_x;
     const unsigned lds_w_addr = (unsigned)(uintptr_t)(lds_ptr)lds_w;
+    int8_t* const lds_sc = lds + kLdsBytes;  // the tile's scales and bias, fetched during the mainloop
+    const unsigned lds_sc_addr = (unsigned)(uintptr_t)(lds_ptr)lds_sc;
 
     // ---- which tile ------------------------------------------------------
     const int pid = blockIdx.x;
@@ -214,19 +218,18 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         }
     }
 
+    // The loads of a stage are issued in four parts, one per K step of the stage being
+    // multiplied, so that no wave sits in a queue of eight loads while the MFMA pipe idles.
+    auto issue_part = [&](int st, int k0, int j) {
+        load_to_lds_16(rsrc_x, lds_x_addr + st * kXStage + (wave + 8 * j) * 1024, voff_x[j], k0);
+        if (W_BITS == 8)
+            load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0);
+        else if (j < 2)
+            load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0 / 2);
+    };
     auto issue_stage = [&](int st, int k0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            load_to_lds_16(rsrc_x, lds_x_addr + st * kXStage + (wave + 8 * j) * 1024, voff_x[j], k0);
-        if (W_BITS == 8) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0 / 2);
-        }
+        for (int j = 0; j < 4; ++j) issue_part(st, k0, j);
     };
 
     // ---- LDS -> MFMA operand mapping -----------------------------------------
@@ -255,48 +258,85 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
 
     const int nk = (K + kTileK - 1) / kTileK;
 
+    // Scales and bias of the tile: threads 0..255 fetch one channel and one token each
+    // here and park them in LDS after the first stage has been multiplied, so that the
+    // epilogue finds them on chip.  Entries past N or M, and a missing bias, are zero.
+    float pre_ws = 0.0f, pre_xs = 0.0f;
+    _Float16 pre_b = (_Float16)0.0f;
+    if (tid < 256) {
+        if (ch0 + tid < a.N) {
+            pre_ws = a.w_scale[ch0 + tid];
+            if (a.bias) pre_b = a.bias[ch0 + tid];
+        }
+        if (tok0 + tid < a.M) pre_xs = a.x_scale[tok0 + tid];
+    }
+
     issue_stage(0, 0);
     for (int it = 0; it < nk; ++it) {
         const int st = it & 1;
         // Stage `it` has landed for every wave, and every wave is done reading
         // stage it-1, whose buffer the loads issued next overwrite.
         wait_loads_and_barrier();
-        if (it + 1 < nk) issue_stage(st ^ 1, (it + 1) * kTileK);
-        if (!wave_live) continue;
+        const bool more = it + 1 < nk;
+        if (it == 1 && tid < 256) {  // (the values were requested a whole stage ago)
+            *(float*)(lds_sc + tid * 4) = pre_ws;
+            *(_Float16*)(lds_sc + 1024 + tid * 2) = pre_b;
+            *(float*)(lds_sc + 2048 + tid * 4) = pre_xs;
+        }
+        if (!wave_live) {  // nothing to multiply, but this wave's share of the loads is needed
+            if (more) issue_stage(st ^ 1, (it + 1) * kTileK);
+            continue;
+        }
 
         const int8_t* xs = lds_x + st * kXStage;
         const int8_t* ws = lds_w + st * kWStage;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            v4i xf[4], wf[2];
+        // Operand registers are double buffered: the LDS reads of K step ks+1 are
+        // issued before the MFMAs of step ks, which cover their latency.
+        v4i xf[2][4], wf[2][2];
+        auto read_step = [&](int ks, v4i(&xo)[4], v4i(&wo)[2]) {
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 if (W_BITS == 8)
-                    wf[cb] = *(const v4i*)(ws + w_off[ks] + cb * 32 * kTileK);
+                    wo[cb] = *(const v4i*)(ws + w_off[ks] + cb * 32 * kTileK);
                 else
-                    wf[cb] = widen_nibbles(*(const v2i*)(ws + w_off[ks] + cb * 32 * (kTileK / 2)));
+                    wo[cb] = widen_nibbles(*(const v2i*)(ws + w_off[ks] + cb * 32 * (kTileK / 2)));
             }
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb) xf[tb] = *(const v4i*)(xs + x_off[ks] + tb * 32 * kTileK);
+            for (int tb = 0; tb < 4; ++tb) xo[tb] = *(const v4i*)(xs + x_off[ks] + tb * 32 * kTileK);
             if (K_TAIL && it == nk - 1) {
                 // K is a multiple of 16 but not of 128: chunks past K hold bytes of the
                 // next row (or nothing); a zero weight operand removes them.
                 if (it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K) {
 #pragma unroll
-                    for (int cb = 0; cb < 2; ++cb) wf[cb] = v4i{0, 0, 0, 0};
+                    for (int cb = 0; cb < 2; ++cb) wo[cb] = v4i{0, 0, 0, 0};
                 }
             }
+        };
+        read_step(0, xf[0], wf[0]);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) read_step(ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+            if (more) issue_part(st ^ 1, (it + 1) * kTileK, ks);
+            // nothing moves across: the reads above stay ahead of the MFMAs below (the
+            // scheduler would otherwise sink them next to their uses to save registers)
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
                 for (int tb = 0; tb < 4; ++tb)
-                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[cb], xf[tb], acc[cb][tb], 0, 0, 0);
+                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][cb], xf[ks & 1][tb],
+                                                                        acc[cb][tb], 0, 0, 0);
         }
     }
 
     // ---- epilogue ------------------------------------------------------------
     // Lane (h = lane/32, t = lane%32) holds, for each of its 4 token blocks, the
     // 32 channels chl .. chl+31: accumulator block b, register r <-> chl + 16 b + r.
+    if (nk == 1 && tid < 256) {
+        *(float*)(lds_sc + tid * 4) = pre_ws;
+        *(_Float16*)(lds_sc + 1024 + tid * 2) = pre_b;
+        *(float*)(lds_sc + 2048 + tid * 4) = pre_xs;
+    }
     wait_loads_and_barrier();  // the stage buffers are free: they become the staging area
     if (!wave_live) return;
     const int h = lane >> 5;
@@ -306,46 +346,25 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     // the 4-bit path accumulated 16 * w: fold the exact 1/16 into the channel scale
     const float wmul = (W_BITS == 4) ? 0.0625f : 1.0f;
 
-    float wsc[32], bsc[32];
-    if (vec) {
+    float wsc[32];
+    half8 bh[4];
+    const int8_t* sc_w = lds_sc + (wave_c * 64 + 32 * h) * 4;
+    const int8_t* sc_b = lds_sc + 1024 + (wave_c * 64 + 32 * h) * 2;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            if (ch + 8 * g < a.N) {
-                const v4f s0 = *(const v4f*)(a.w_scale + ch + 8 * g);
-                const v4f s1 = *(const v4f*)(a.w_scale + ch + 8 * g + 4);
+    for (int g = 0; g < 8; ++g) {
+        const v4f sv = *(const v4f*)(sc_w + 16 * g);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    wsc[8 * g + e] = s0[e] * wmul;
-                    wsc[8 * g + 4 + e] = s1[e] * wmul;
-                }
-                if (a.bias) {
-                    const half8 bv = *(const half8*)(a.bias + ch + 8 * g);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) bsc[8 * g + e] = (float)bv[e];
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) bsc[8 * g + e] = 0.0f;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) wsc[8 * g + e] = 0.0f, bsc[8 * g + e] = 0.0f;
-            }
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < 32; ++q) {
-            const bool ok = ch + q < a.N;
-            wsc[q] = ok ? a.w_scale[ch + q] * wmul : 0.0f;
-            bsc[q] = (ok && a.bias) ? (float)a.bias[ch + q] : 0.0f;
-        }
+        for (int e = 0; e < 4; ++e) wsc[4 * g + e] = sv[e] * wmul;
     }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) bh[g] = *(const half8*)(sc_b + 16 * g);
 
     int8_t* const stage = lds + wave * kEpiWave;  // this wave's 64 tokens x (128 + 16) bytes
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
         const long tok = tok0 + wave_t * 128 + tb * 32 + (lane & 31);
         const bool tok_ok = tok < a.M;
-        const float xsc = tok_ok ? a.x_scale[tok] : 0.0f;
+        const float xsc = *(const float*)(lds_sc + 2048 + (wave_t * 128 + tb * 32 + (lane & 31)) * 4);
         _Float16* yrow = a.y + tok * a.N + ch;
         int32_t* arow = a.acc_out ? a.acc_out + tok * a.N + ch : nullptr;
 #pragma unroll
@@ -357,10 +376,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             for (int e = 0; e < 8; ++e) {
                 const int v = acc[b][tb][r0 + e];
                 iv[e] = (W_BITS == 4) ? (v >> 4) : v;
-                float f = (float)v * xsc;
-                f = f * wsc[8 * g + e];
-                f = f + bsc[8 * g + e];
-                out[e] = (_Float16)f;
+                const float f = (float)v * xsc;
+                out[e] = (_Float16)__builtin_fmaf(f, wsc[8 * g + e], (float)bh[g][e]);
             }
             if (vec) {
                 // staged: token row (tb%2)*32 + t, byte column 64 h + 16 g
