@@ -15,16 +15,21 @@ inline bool misaligned(const void* p) { return ((uintptr_t)p % kAlign) != 0; }
 // 0 = not looked at yet, 1 = gfx950, 2 = something else.  A benign cache: the
 // answer for a device ordinal never changes during the life of the process.
 std::atomic<int> g_arch_state[kMaxDevices];
+std::atomic<int> g_num_cus[kMaxDevices];
 
-int check_arch() {
+// VQ_OK if the current device is gfx950; *num_cus (if asked for) gets its CU count.
+int check_arch(int* num_cus = nullptr) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
         (void)hipGetLastError();
         return VQ_ERR_ARCH;
     }
     if (dev < kMaxDevices) {
-        const int s = g_arch_state[dev].load(std::memory_order_relaxed);
-        if (s == 1) return VQ_OK;
+        const int s = g_arch_state[dev].load(std::memory_order_acquire);
+        if (s == 1) {
+            if (num_cus) *num_cus = g_num_cus[dev].load(std::memory_order_relaxed);
+            return VQ_OK;
+        }
         if (s == 2) return VQ_ERR_ARCH;
     }
     hipDeviceProp_t prop;
@@ -35,7 +40,11 @@ int check_arch() {
     const char* name = prop.gcnArchName;  // e.g. "gfx950:sramecc+:xnack-"
     const bool ok = name[0] == 'g' && name[1] == 'f' && name[2] == 'x' && name[3] == '9' &&
                     name[4] == '5' && name[5] == '0' && (name[6] == '\0' || name[6] == ':');
-    if (dev < kMaxDevices) g_arch_state[dev].store(ok ? 1 : 2, std::memory_order_relaxed);
+    if (num_cus) *num_cus = prop.multiProcessorCount;
+    if (dev < kMaxDevices) {
+        g_num_cus[dev].store(prop.multiProcessorCount, std::memory_order_relaxed);
+        g_arch_state[dev].store(ok ? 1 : 2, std::memory_order_release);
+    }
     return ok ? VQ_OK : VQ_ERR_ARCH;
 }
 
@@ -61,10 +70,11 @@ int gemm_entry(const int8_t* xq, const float* x_scale, const void* w, int w_bits
     const int v = validate_gemm(xq, x_scale, w, w_scale, bias_f16, y_f16, acc_out, w_bits, M, N, K);
     if (v != VQ_OK) return v;
     if (M == 0 || N == 0) return VQ_OK;
-    const int arch = check_arch();
+    int num_cus = 0;
+    const int arch = check_arch(&num_cus);
     if (arch != VQ_OK) return arch;
     return launch_status(vq::launch_gemm(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, acc_out,
-                                         M, N, K, (hipStream_t)hip_stream));
+                                         M, N, K, num_cus, (hipStream_t)hip_stream));
 }
 
 int validate_quantize(const void* x, const void* chan_mul, const void* xq, const void* x_scale,
@@ -129,13 +139,14 @@ int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bit
     if (v != VQ_OK) return v;
     v = validate_gemm(xq, x_scale, w, w_scale, bias_f16, y_f16, nullptr, w_bits, M, N, K);
     if (v != VQ_OK) return v;
-    const int arch = check_arch();
+    int num_cus = 0;
+    const int arch = check_arch(&num_cus);
     if (arch != VQ_OK) return arch;
     hipStream_t stream = (hipStream_t)hip_stream;
     v = launch_status(vq::launch_quantize_per_token(x_f16, chan_mul, xq, x_scale, M, K, stream));
     if (v != VQ_OK) return v;
     return launch_status(vq::launch_gemm(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, nullptr,
-                                         M, N, K, stream));
+                                         M, N, K, num_cus, stream));
 }
 
 int vq_quantize_weight(const float* w_f32, const float* chan_s, int w_bits, void* wq_out,

@@ -32,17 +32,22 @@
 //     scales and narrows in registers, turns each wavefront's 128 x 64 block
 //     through LDS and writes whole 128-byte lines of Y, bypassing the caches'
 //     retention (nontemporal): the operands keep the L2.
-//   - Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the
-//     id is remapped so that each XCD works on a contiguous run of tiles,
-//     ordered in bands of 8 token tiles, and its L2 sees each panel once.
+//   - The kernel is persistent: one workgroup per CU walks a list of tiles.
+//     The first stage of the next tile is requested while the last stage of
+//     the current one is multiplied, and the epilogue (which stages through
+//     the buffer just consumed) runs while those loads are in flight.
+//   - Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; each
+//     XCD gets a contiguous run of tiles, ordered in bands of 8 token tiles,
+//     and the workgroups of an XCD take them in turn, so that its L2 sees each
+//     operand panel once.
 //
 // Integer accumulation is exact and order independent, so the result is the
 // same whatever the tiling; the 4-bit path multiplies by 16 * w (nibble left in
 // the high half of the byte) and divides the sum by 16 exactly afterwards.
 //
-// The epilogue computes fp16(fma(float(acc) * x_scale, w_scale, bias)) in fp32: one
-// rounding fewer than the three separate operations, so an output can differ from
-// the separately rounded value in the last fp16 place.
+// The epilogue computes fp16_rne(fma_f32(float(acc) * x_scale, w_scale, bias)): one fp32
+// rounding fewer than three separate operations, so an output can differ from the
+// separately rounded value in the last fp16 place.
 #include "vq_internal.h"
 
 namespace vq {
@@ -65,12 +70,11 @@ constexpr int kWStage = kTileC * kTileK;    // 32 KiB (16 KiB used by packed 4-b
 constexpr int kStages = 2;
 constexpr int kLdsBytes = kStages * (kXStage + kWStage);  // 128 KiB
 constexpr int kScaleBytes = 3 * 1024;       // w_scale[256] fp32 | bias[256] fp16 (+pad) | x_scale[256] fp32
-constexpr int kEpiRow = 128 + 16;           // bytes per token row of the epilogue staging (padded)
-constexpr int kEpiWave = 64 * kEpiRow;      // one wavefront stages 64 tokens x 64 channels at a time
+constexpr int kEpiWave = 64 * 128;          // a wavefront stages 64 tokens x 64 channels of fp16 at a time
 constexpr int kBand = 8;                    // token tiles per band in the tile order
 constexpr int kXcds = 8;
 constexpr unsigned kRsrcFlags = 0x00020000; // raw buffer, 32-bit data format
-static_assert(kWaves * kEpiWave <= kLdsBytes, "epilogue staging must fit the stage buffers");
+static_assert(kWaves * kEpiWave == kXStage + kWStage, "epilogue staging is one stage buffer pair");
 
 struct GemmArgs {
     const int8_t* xq;
@@ -82,6 +86,7 @@ struct GemmArgs {
     int32_t* acc_out;
     int M, N, K;
     int tiles_t, tiles_c, tiles, tiles_per_xcd;
+    int slots;  // workgroups per XCD; workgroup (xcd, slot) takes tiles slot, slot + slots, ... of its XCD
 };
 
 // LDS row r of the weight tile holds which output channel of the tile.
@@ -124,10 +129,15 @@ __device__ __forceinline__ void load_to_lds_16(v4i rsrc, unsigned lds_addr, int 
         : "memory");
 }
 
-// Waits until all of this wave's direct loads have landed and all its LDS
-// accesses are done, then joins the workgroup barrier.
+// Waits until all of this wave's direct loads (and stores) have completed and all
+// its LDS accesses are done, then joins the workgroup barrier.
 __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" : : : "memory");
+}
+
+// Barrier for LDS traffic only: loads in flight stay in flight.
+__device__ __forceinline__ void wait_lds_and_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory");
 }
 
 // 16 nibbles (two dwords) -> 16 bytes holding 16 * w: the nibble is moved to
@@ -145,32 +155,37 @@ __device__ __forceinline__ v4i widen_nibbles(v2i p) {
     return o;
 }
 
-// K_TAIL: K is a multiple of 16 but not of 128 (the last stage is partly past K).
-template <int W_BITS, bool K_TAIL>
+// Returns v unchanged but opaque to the optimiser: what is derived from the result is
+// recomputed where it is used instead of being kept in registers across the mainloop.
+__device__ __forceinline__ int opaque(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+// Where a tile sits in the output (wave-uniform).
+struct TilePos {
+    long tok0, ch0;
+    int rows_x, rows_w;  // rows of the tile that exist (the rest is clamped on load, masked on store)
+};
+// What this wave's share of a tile's loads needs: buffer descriptors and per-lane offsets.
+struct TileLoads {
+    v4i rsrc_x, rsrc_w;
+    int voff_x[4], voff_w[4];
+};
+
+// K_TAIL:  K is a multiple of 16 but not of 128 (the last stage is partly past K).
+// GENERIC: any N and an optional copy of the integer sums; stores go out element by
+//          element.  The fast variant needs N % 8 == 0 and writes whole lines.
+template <int W_BITS, bool K_TAIL, bool GENERIC>
 __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a) {
     __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes + kScaleBytes];
-    // layout: [X stage 0][X stage 1][W stage 0][W stage 1]; a W stage is
+    // layout: [X buffer 0][X buffer 1][W buffer 0][W buffer 1][scales]; a W buffer is
     // [256 rows][128 B] of int8 or, for 4-bit weights, [256 rows][64 B] of nibbles.
     int8_t* const lds_x = lds;
     int8_t* const lds_w = lds + kStages * kXStage;
     const unsigned lds_x_addr = (unsigned)(uintptr_t)(lds_ptr)lds_x;
     const unsigned lds_w_addr = (unsigned)(uintptr_t)(lds_ptr)lds_w;
-    int8_t* const lds_sc = lds + kLdsBytes;  // the tile's scales and bias, fetched during the mainloop
-    const unsigned lds_sc_addr = (unsigned)(uintptr_t)(lds_ptr)lds_sc;
-
-    // ---- which tile ------------------------------------------------------
-    const int pid = blockIdx.x;
-    const int logical = (pid % kXcds) * a.tiles_per_xcd + pid / kXcds;
-    if (pid / kXcds >= a.tiles_per_xcd || logical >= a.tiles) return;  // uniform per workgroup
-    const int band_tiles = kBand * a.tiles_c;
-    const int band = logical / band_tiles;
-    const int band_first = band * kBand;
-    const int band_rows = min(a.tiles_t - band_first, kBand);
-    const int in_band = logical - band * band_tiles;
-    const int tile_t = band_first + in_band % band_rows;
-    const int tile_c = in_band / band_rows;
-    const long tok0 = (long)tile_t * kTileT;
-    const long ch0 = (long)tile_c * kTileC;
+    int8_t* const lds_sc = lds + kLdsBytes;  // w_scale | bias | x_scale of the current tile
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -180,17 +195,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     // leaves one working wave on every SIMD.
     const int wave_t = wave & 1;   // which 128 tokens
     const int wave_c = wave >> 1;  // which 64 channels
-
     const int K = a.K;
-    const int rows_x = (int)min((long)kTileT, a.M - tok0);
-    const int rows_w = (int)min((long)kTileC, a.N - ch0);
-    // a wave whose 64 channels (or 128 tokens) lie wholly past the matrix has nothing to multiply
-    const bool wave_live = (wave_c * 64 < rows_w) && (wave_t * 128 < rows_x);
-
     constexpr int kWDiv = (W_BITS == 8) ? 1 : 2;  // values of K per stored byte
-    const v4i rsrc_x = make_rsrc(a.xq + tok0 * K, clamp_u32((a.M - tok0) * (long)K));
-    const v4i rsrc_w = make_rsrc((const int8_t*)a.w + ch0 * (K / kWDiv),
-                                 clamp_u32((a.N - ch0) * (long)(K / kWDiv)));
+    const int nk = (K + kTileK - 1) / kTileK;
 
     // ---- global -> LDS mapping ---------------------------------------------
     // One direct load fills 1 KiB; lane l writes bytes [16 l, 16 l + 16).
@@ -198,221 +205,267 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     // which under the swizzle holds logical chunk (l%8) ^ ((row/2)%8).  Wave w
     // loads row groups w, w+8, w+16, w+24 of each tile, so row/2 mod 8 is
     // (4 (w%2) + l/16) % 8 for all of them.
-    const int ld_row = lane >> 3;
-    const int ld_chunk = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
-    int voff_x[4], voff_w[4];
+    // Packed 4-bit tile [256 rows][64 B]: 16 rows x 64 B per load, lane l = row l/4,
+    // physical chunk l%4 holding logical chunk (l%4) ^ ((row/4)%4) = (l%4) ^ (l/16);
+    // wave w loads row groups w and w+8.
+    auto decode_tile = [&](int idx, TilePos& t, TileLoads& ld) {
+        const int l = opaque(lane);
+        const int ld_chunk16 = ((l & 7) ^ ((4 * (wave & 1) + (l >> 4)) & 7)) << 4;
+        const int ld_chunk16_w4 = ((l & 3) ^ (l >> 4)) << 4;
+        const int logical = (blockIdx.x % kXcds) * a.tiles_per_xcd + idx;
+        const int band_tiles = kBand * a.tiles_c;
+        const int band = logical / band_tiles;
+        const int band_first = band * kBand;
+        const int band_rows = min(a.tiles_t - band_first, kBand);
+        const int in_band = logical - band * band_tiles;
+        t.tok0 = (long)(band_first + in_band % band_rows) * kTileT;
+        t.ch0 = (long)(in_band / band_rows) * kTileC;
+        t.rows_x = (int)min((long)kTileT, a.M - t.tok0);
+        t.rows_w = (int)min((long)kTileC, a.N - t.ch0);
+        ld.rsrc_x = make_rsrc(a.xq + t.tok0 * K, clamp_u32((a.M - t.tok0) * (long)K));
+        ld.rsrc_w = make_rsrc((const int8_t*)a.w + t.ch0 * (K / kWDiv),
+                              clamp_u32((a.N - t.ch0) * (long)(K / kWDiv)));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int r = (wave + 8 * j) * 8 + ld_row;
-        voff_x[j] = min(r, rows_x - 1) * K + ld_chunk * 16;
-        voff_w[j] = min(w_row_to_channel(r), rows_w - 1) * K + ld_chunk * 16;
-    }
-    if (W_BITS == 4) {
-        // packed tile [256 rows][64 B]: 16 rows x 64 B per load, lane l = row l/4,
-        // physical chunk l%4 holding logical chunk (l%4) ^ ((row/4)%4) = (l%4) ^ (l/16).
-        // Wave w loads row groups w and w+8.
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int r = (wave + 8 * j) * 16 + (lane >> 2);
-            voff_w[j] = min(w_row_to_channel(r), rows_w - 1) * (K / 2) + (((lane & 3) ^ (lane >> 4)) << 4);
+        for (int j = 0; j < 4; ++j) {
+            const int r = (wave + 8 * j) * 8 + (l >> 3);
+            ld.voff_x[j] = min(r, t.rows_x - 1) * K + ld_chunk16;
+            if (W_BITS == 8) {
+                ld.voff_w[j] = min(w_row_to_channel(r), t.rows_w - 1) * K + ld_chunk16;
+            } else {
+                const int r4 = (wave + 8 * (j & 1)) * 16 + (l >> 2);
+                ld.voff_w[j] = min(w_row_to_channel(r4), t.rows_w - 1) * (K / 2) + ld_chunk16_w4;
+            }
         }
-    }
-
-    // The loads of a stage are issued in four parts, one per K step of the stage being
-    // multiplied, so that no wave sits in a queue of eight loads while the MFMA pipe idles.
-    auto issue_part = [&](int st, int k0, int j) {
-        load_to_lds_16(rsrc_x, lds_x_addr + st * kXStage + (wave + 8 * j) * 1024, voff_x[j], k0);
-        if (W_BITS == 8)
-            load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0);
-        else if (j < 2)
-            load_to_lds_16(rsrc_w, lds_w_addr + st * kWStage + (wave + 8 * j) * 1024, voff_w[j], k0 / 2);
     };
-    auto issue_stage = [&](int st, int k0) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) issue_part(st, k0, j);
+    auto tile_exists = [&](int idx) {
+        return idx < a.tiles_per_xcd && (int)(blockIdx.x % kXcds) * a.tiles_per_xcd + idx < a.tiles;
+    };
+
+    // One quarter of a stage's loads (this wave's share): issued between the K steps of
+    // the stage being multiplied, so that no wave sits in a queue of eight loads.
+    auto issue_part = [&](const TileLoads& ld, int buf, int k0, int j) {
+        load_to_lds_16(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
+        if (W_BITS == 8)
+            load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j], k0);
+        else if (j < 2)
+            load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
+                           k0 / 2);
     };
 
     // ---- LDS -> MFMA operand mapping -----------------------------------------
     // Operand rows of a 32x32x32 block: lane l supplies row l%32, 16 bytes of K
     // chosen by l/32; a stage holds four such K steps (chunks 2ks and 2ks+1).
+    // The chunk index of K step ks is (2 ks + l/32) ^ swizzle = ((l/32) ^ swizzle) ^ 2 ks, so the
+    // byte offset of step ks is that of step 0 with 32 ks XOR-ed in.
     const int fr_row = lane & 31;
-    int x_off[4], w_off[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        const int phys = ((2 * ks + (lane >> 5)) ^ ((fr_row >> 1) & 7)) << 4;
-        x_off[ks] = (wave_t * 128 + fr_row) * kTileK + phys;
-        if (W_BITS == 8)
-            w_off[ks] = (wave_c * 64 + fr_row) * kTileK + phys;
-        else  // 8 bytes of nibbles: 16-byte chunk ks (swizzled by (row/4)%4), half l/32
-            w_off[ks] = (wave_c * 64 + fr_row) * (kTileK / 2) + ((ks ^ ((fr_row >> 2) & 3)) << 4) +
-                        (lane >> 5) * 8;
-    }
+    const int x_off0 = (wave_t * 128 + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4);
+    const int w_off0 = (W_BITS == 8)
+                           ? (wave_c * 64 + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4)
+                           // 8 bytes of nibbles: 16-byte chunk ks (swizzled by (row/4)%4), half l/32
+                           : (wave_c * 64 + fr_row) * (kTileK / 2) + (((fr_row >> 2) & 3) << 4) + (lane >> 5) * 8;
+    auto x_off = [&](int ks) { return x_off0 ^ (ks << 5); };
+    auto w_off = [&](int ks) { return w_off0 ^ (ks << (W_BITS == 8 ? 5 : 4)); };
 
-    v16i acc[2][4];
+    // ---- the tiles of this workgroup -------------------------------------------
+    int idx = blockIdx.x / kXcds;
+    if (!tile_exists(idx)) return;  // uniform per workgroup
+    TilePos cur;   // the tile being multiplied
+    TileLoads ld;  // the tile whose stages are being requested (the next one during the last stage)
+    decode_tile(idx, cur, ld);
+    int buf = 0;  // LDS buffer of the stage about to be multiplied
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[cb][tb][r] = 0;
+    for (int j = 0; j < 4; ++j) issue_part(ld, 0, 0, j);
 
-    const int nk = (K + kTileK - 1) / kTileK;
+    while (true) {
+        const int next_idx = idx + a.slots;
+        const bool has_next = tile_exists(next_idx);
+        TilePos nxt = cur;
 
-    // Scales and bias of the tile: threads 0..255 fetch one channel and one token each
-    // here and park them in LDS after the first stage has been multiplied, so that the
-    // epilogue finds them on chip.  Entries past N or M, and a missing bias, are zero.
-    float pre_ws = 0.0f, pre_xs = 0.0f;
-    _Float16 pre_b = (_Float16)0.0f;
-    if (tid < 256) {
-        if (ch0 + tid < a.N) {
-            pre_ws = a.w_scale[ch0 + tid];
-            if (a.bias) pre_b = a.bias[ch0 + tid];
-        }
-        if (tok0 + tid < a.M) pre_xs = a.x_scale[tok0 + tid];
-    }
+        // a wave whose 64 channels (or 128 tokens) lie wholly past the matrix has nothing to multiply
+        const bool wave_live = (wave_c * 64 < cur.rows_w) && (wave_t * 128 < cur.rows_x);
 
-    issue_stage(0, 0);
-    for (int it = 0; it < nk; ++it) {
-        const int st = it & 1;
-        // Stage `it` has landed for every wave, and every wave is done reading
-        // stage it-1, whose buffer the loads issued next overwrite.
-        wait_loads_and_barrier();
-        const bool more = it + 1 < nk;
-        if (it == 1 && tid < 256) {  // (the values were requested a whole stage ago)
-            *(float*)(lds_sc + tid * 4) = pre_ws;
-            *(_Float16*)(lds_sc + 1024 + tid * 2) = pre_b;
-            *(float*)(lds_sc + 2048 + tid * 4) = pre_xs;
-        }
-        if (!wave_live) {  // nothing to multiply, but this wave's share of the loads is needed
-            if (more) issue_stage(st ^ 1, (it + 1) * kTileK);
-            continue;
-        }
-
-        const int8_t* xs = lds_x + st * kXStage;
-        const int8_t* ws = lds_w + st * kWStage;
-        // Operand registers are double buffered: the LDS reads of K step ks+1 are
-        // issued before the MFMAs of step ks, which cover their latency.
-        v4i xf[2][4], wf[2][2];
-        auto read_step = [&](int ks, v4i(&xo)[4], v4i(&wo)[2]) {
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
-                if (W_BITS == 8)
-                    wo[cb] = *(const v4i*)(ws + w_off[ks] + cb * 32 * kTileK);
-                else
-                    wo[cb] = widen_nibbles(*(const v2i*)(ws + w_off[ks] + cb * 32 * (kTileK / 2)));
+        // Scales and bias of the tile: threads 0..255 fetch one channel and one token each
+        // here and park them in LDS after the mainloop, where every lane of the epilogue
+        // finds them.  Entries past N or M, and a missing bias, are zero.
+        float pre_ws = 0.0f, pre_xs = 0.0f;
+        _Float16 pre_b = (_Float16)0.0f;
+        if (wave < 4) {
+            const int i = wave * 64 + opaque(lane);
+            if (cur.ch0 + i < a.N) {
+                pre_ws = a.w_scale[cur.ch0 + i];
+                if (a.bias) pre_b = a.bias[cur.ch0 + i];
             }
+            if (cur.tok0 + i < a.M) pre_xs = a.x_scale[cur.tok0 + i];
+        }
+
+        v16i acc[2][4];
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb) xo[tb] = *(const v4i*)(xs + x_off[ks] + tb * 32 * kTileK);
-            if (K_TAIL && it == nk - 1) {
-                // K is a multiple of 16 but not of 128: chunks past K hold bytes of the
-                // next row (or nothing); a zero weight operand removes them.
-                if (it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K) {
+        for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-                    for (int cb = 0; cb < 2; ++cb) wo[cb] = v4i{0, 0, 0, 0};
+            for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[cb][tb][r] = 0;
+
+        for (int it = 0; it < nk; ++it) {
+            // Stage `it` has landed for every wave, and every wave is done with the other
+            // buffer (stage it-1, or the previous tile's epilogue staging), which the loads
+            // issued next overwrite.
+            wait_loads_and_barrier();
+            // what to request while this stage is multiplied: the next stage of this tile,
+            // or the first stage of the next tile
+            const bool more = it + 1 < nk;
+            const bool fetch = more || has_next;
+            if (!more && has_next) decode_tile(next_idx, nxt, ld);
+            const int fk0 = more ? (it + 1) * kTileK : 0;
+
+            if (!wave_live) {  // nothing to multiply, but this wave's share of the loads is needed
+                if (fetch) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) issue_part(ld, buf ^ 1, fk0, j);
                 }
+                buf ^= 1;
+                continue;
             }
-        };
-        read_step(0, xf[0], wf[0]);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < 3) read_step(ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
-            if (more) issue_part(st ^ 1, (it + 1) * kTileK, ks);
-            // nothing moves across: the reads above stay ahead of the MFMAs below (the
-            // scheduler would otherwise sink them next to their uses to save registers)
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int tb = 0; tb < 4; ++tb)
-                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][cb], xf[ks & 1][tb],
-                                                                        acc[cb][tb], 0, 0, 0);
-        }
-    }
 
-    // ---- epilogue ------------------------------------------------------------
-    // Lane (h = lane/32, t = lane%32) holds, for each of its 4 token blocks, the
-    // 32 channels chl .. chl+31: accumulator block b, register r <-> chl + 16 b + r.
-    if (nk == 1 && tid < 256) {
-        *(float*)(lds_sc + tid * 4) = pre_ws;
-        *(_Float16*)(lds_sc + 1024 + tid * 2) = pre_b;
-        *(float*)(lds_sc + 2048 + tid * 4) = pre_xs;
-    }
-    wait_loads_and_barrier();  // the stage buffers are free: they become the staging area
-    if (!wave_live) return;
-    const int h = lane >> 5;
-    const long chw = ch0 + wave_c * 64;  // first channel of this wave
-    const long ch = chw + 32 * h;        // first channel of this lane
-    const bool vec = (a.N % 8) == 0;
-    // the 4-bit path accumulated 16 * w: fold the exact 1/16 into the channel scale
-    const float wmul = (W_BITS == 4) ? 0.0625f : 1.0f;
-
-    float wsc[32];
-    half8 bh[4];
-    const int8_t* sc_w = lds_sc + (wave_c * 64 + 32 * h) * 4;
-    const int8_t* sc_b = lds_sc + 1024 + (wave_c * 64 + 32 * h) * 2;
+            const int8_t* xs = lds_x + buf * kXStage;
+            const int8_t* ws = lds_w + buf * kWStage;
+            // Operand registers are double buffered: the LDS reads of K step ks+1 are
+            // issued before the MFMAs of step ks, which cover their latency.
+            v4i xf[2][4], wf[2][2];
+            auto read_step = [&](int ks, v4i(&xo)[4], v4i(&wo)[2]) {
 #pragma unroll
-    for (int g = 0; g < 8; ++g) {
-        const v4f sv = *(const v4f*)(sc_w + 16 * g);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) wsc[4 * g + e] = sv[e] * wmul;
-    }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) bh[g] = *(const half8*)(sc_b + 16 * g);
-
-    int8_t* const stage = lds + wave * kEpiWave;  // this wave's 64 tokens x (128 + 16) bytes
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
-        const long tok = tok0 + wave_t * 128 + tb * 32 + (lane & 31);
-        const bool tok_ok = tok < a.M;
-        const float xsc = *(const float*)(lds_sc + 2048 + (wave_t * 128 + tb * 32 + (lane & 31)) * 4);
-        _Float16* yrow = a.y + tok * a.N + ch;
-        int32_t* arow = a.acc_out ? a.acc_out + tok * a.N + ch : nullptr;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int b = g >> 1, r0 = (g & 1) * 8;
-            half8 out;
-            int iv[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int v = acc[b][tb][r0 + e];
-                iv[e] = (W_BITS == 4) ? (v >> 4) : v;
-                const float f = (float)v * xsc;
-                out[e] = (_Float16)__builtin_fmaf(f, wsc[8 * g + e], (float)bh[g][e]);
-            }
-            if (vec) {
-                // staged: token row (tb%2)*32 + t, byte column 64 h + 16 g
-                *(half8*)(stage + ((tb & 1) * 32 + (lane & 31)) * kEpiRow + 64 * h + 16 * g) = out;
-                if (arow && tok_ok && ch + 8 * g < a.N) {
-                    *(v4i*)(arow + 8 * g) = v4i{iv[0], iv[1], iv[2], iv[3]};
-                    *(v4i*)(arow + 8 * g + 4) = v4i{iv[4], iv[5], iv[6], iv[7]};
+                for (int cb = 0; cb < 2; ++cb) {
+                    if (W_BITS == 8)
+                        wo[cb] = *(const v4i*)(ws + w_off(ks) + cb * 32 * kTileK);
+                    else
+                        wo[cb] = widen_nibbles(*(const v2i*)(ws + w_off(ks) + cb * 32 * (kTileK / 2)));
                 }
-            } else if (tok_ok) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    if (ch + 8 * g + e < a.N) {
-                        yrow[8 * g + e] = out[e];
-                        if (arow) arow[8 * g + e] = iv[e];
+                for (int tb = 0; tb < 4; ++tb) xo[tb] = *(const v4i*)(xs + x_off(ks) + tb * 32 * kTileK);
+                if (K_TAIL && it == nk - 1) {
+                    // K is a multiple of 16 but not of 128: chunks past K hold bytes of the
+                    // next row (or nothing); a zero weight operand removes them.
+                    if (it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K) {
+#pragma unroll
+                        for (int cb = 0; cb < 2; ++cb) wo[cb] = v4i{0, 0, 0, 0};
                     }
                 }
-            }
-        }
-        if (vec && (tb & 1)) {
-            // 64 token rows x 128 B are staged: write them out a full line per 8 lanes.
-            // Only this wave touches its staging area; LDS operations of a wave execute
-            // in order, the fence only keeps the compiler from reordering them.
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            };
+            read_step(0, xf[0], wf[0]);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = i * 8 + (lane >> 3);
-                const half8 v = *(const half8*)(stage + row * kEpiRow + (lane & 7) * 16);
-                const long t = tok0 + wave_t * 128 + (tb - 1) * 32 + row;
-                const long c = chw + (lane & 7) * 8;
-                if (t < a.M && c < a.N) __builtin_nontemporal_store(v, (half8*)(a.y + t * a.N + c));
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < 3) read_step(ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+                if (fetch) issue_part(ld, buf ^ 1, fk0, ks);
+                // nothing moves across: the reads above stay ahead of the MFMAs below (the
+                // scheduler would otherwise sink them next to their uses to save registers)
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int tb = 0; tb < 4; ++tb)
+                        acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][cb], xf[ks & 1][tb],
+                                                                            acc[cb][tb], 0, 0, 0);
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            buf ^= 1;
         }
+        // `buf` now names the buffer the next tile's first stage is landing in; the other
+        // one (the last stage multiplied) becomes the epilogue's staging area.
+        if (wave < 4) {
+            const int i = wave * 64 + opaque(lane);
+            *(float*)(lds_sc + i * 4) = pre_ws;
+            *(_Float16*)(lds_sc + 1024 + i * 2) = pre_b;
+            *(float*)(lds_sc + 2048 + i * 4) = pre_xs;
+        }
+        wait_lds_and_barrier();  // every wave is done reading the last stage; scales are visible
+
+        // ---- epilogue ------------------------------------------------------------
+        // Lane (h = lane/32, t = lane%32) holds, for each of its 4 token blocks, the
+        // 32 channels chl .. chl+31: accumulator block b, register r <-> chl + 16 b + r.
+        if (wave_live) {
+            const int el = opaque(lane);  // (the epilogue's per-lane values are not kept across the mainloop)
+            const int h = el >> 5;
+            const long chw = cur.ch0 + wave_c * 64;  // first channel of this wave
+            // the 4-bit path accumulated 16 * w: fold the exact 1/16 into the channel scale
+            const float wmul = (W_BITS == 4) ? 0.0625f : 1.0f;
+            float wsc[32], bsc[32];
+            const int8_t* sc_w = lds_sc + (wave_c * 64 + 32 * h) * 4;
+            const int8_t* sc_b = lds_sc + 1024 + (wave_c * 64 + 32 * h) * 2;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const v4f sv = *(const v4f*)(sc_w + 16 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) wsc[4 * g + e] = sv[e] * wmul;
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const half8 bv = *(const half8*)(sc_b + 16 * g);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bsc[8 * g + e] = (float)bv[e];
+            }
+
+            // staging: [64 token rows][128 B], 16-byte chunks XOR-ed by (row/2)%8; waves
+            // 0..3 use the X buffer just consumed, waves 4..7 the W buffer.
+            int8_t* const stage = (wave < 4 ? lds_x + (buf ^ 1) * kXStage + wave * kEpiWave
+                                            : lds_w + (buf ^ 1) * kWStage + (wave - 4) * kEpiWave);
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) {
+                const int tl = wave_t * 128 + tb * 32 + (el & 31);  // token within the tile
+                const float xsc = *(const float*)(lds_sc + 2048 + tl * 4);
+                const int srow = (tb & 1) * 32 + (el & 31);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int b = g >> 1, r0 = (g & 1) * 8;
+                    half8 out;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float f = (float)acc[b][tb][r0 + e] * xsc;
+                        float y = __builtin_fmaf(f, wsc[8 * g + e], bsc[8 * g + e]);
+                        // keep the fp32 result as such: the narrowing below then is a plain
+                        // round-to-nearest-even of it in every variant of this kernel (a fused
+                        // multiply-add-narrow instruction would round only once)
+                        asm("" : "+v"(y));
+                        out[e] = (_Float16)y;
+                    }
+                    if (!GENERIC) {
+                        *(half8*)(stage + srow * 128 + (((4 * h + g) ^ ((srow >> 1) & 7)) << 4)) = out;
+                    } else if (tl < cur.rows_x) {
+                        const long tok = cur.tok0 + tl;
+                        const long c0 = chw + 32 * h + 8 * g;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            if (c0 + e < a.N) {
+                                a.y[tok * a.N + c0 + e] = out[e];
+                                if (a.acc_out) {
+                                    const int v = acc[b][tb][r0 + e];
+                                    a.acc_out[tok * a.N + c0 + e] = (W_BITS == 4) ? (v >> 4) : v;
+                                }
+                            }
+                        }
+                    }
+                }
+                if (!GENERIC && (tb & 1)) {
+                    // 64 token rows x 128 B are staged: write them out, a full line per 8 lanes.
+                    // Only this wave touches its staging area and the LDS operations of a wave
+                    // execute in order; the fences only keep the compiler from reordering them.
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int row = i * 8 + (el >> 3);
+                        const half8 v = *(const half8*)(stage + row * 128 + (((el & 7) ^ ((row >> 1) & 7)) << 4));
+                        const int t = wave_t * 128 + (tb - 1) * 32 + row;
+                        const long c = chw + (el & 7) * 8;
+                        if (t < cur.rows_x && c < a.N)
+                            __builtin_nontemporal_store(v, (half8*)(a.y + (cur.tok0 + t) * a.N + c));
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+        if (!has_next) break;
+        cur = nxt;
+        idx = next_idx;
     }
 }
 
@@ -420,7 +473,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
 
 hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, int w_bits,
                        const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out,
-                       int M, int N, int K, hipStream_t stream) {
+                       int M, int N, int K, int num_cus, hipStream_t stream) {
     GemmArgs a;
     a.xq = xq;
     a.x_scale = x_scale;
@@ -438,15 +491,22 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     if (tiles > 0x7FFFFFF0l) return hipErrorInvalidValue;
     a.tiles = (int)tiles;
     a.tiles_per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    const dim3 grid((unsigned)(a.tiles_per_xcd * kXcds)), block(kThreads);
+    // one workgroup per CU (the kernel needs most of a CU's LDS), fewer if there are fewer tiles
+    const int cus_per_xcd = num_cus >= kXcds ? num_cus / kXcds : 1;
+    a.slots = a.tiles_per_xcd < cus_per_xcd ? a.tiles_per_xcd : cus_per_xcd;
+    const dim3 grid((unsigned)(a.slots * kXcds)), block(kThreads);
     const bool tail = (K % kTileK) != 0;
+    const bool generic = (N % 8) != 0 || acc_out != nullptr;
+#define VQ_LAUNCH_GEMM(BITS, TAIL, GEN) \
+    hipLaunchKernelGGL((gemm_i8_dequant<BITS, TAIL, GEN>), grid, block, 0, stream, a)
     if (w_bits == 8) {
-        if (tail) hipLaunchKernelGGL((gemm_i8_dequant<8, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((gemm_i8_dequant<8, false>), grid, block, 0, stream, a);
+        if (tail) { if (generic) VQ_LAUNCH_GEMM(8, true, true); else VQ_LAUNCH_GEMM(8, true, false); }
+        else      { if (generic) VQ_LAUNCH_GEMM(8, false, true); else VQ_LAUNCH_GEMM(8, false, false); }
     } else {
-        if (tail) hipLaunchKernelGGL((gemm_i8_dequant<4, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((gemm_i8_dequant<4, false>), grid, block, 0, stream, a);
+        if (tail) { if (generic) VQ_LAUNCH_GEMM(4, true, true); else VQ_LAUNCH_GEMM(4, true, false); }
+        else      { if (generic) VQ_LAUNCH_GEMM(4, false, true); else VQ_LAUNCH_GEMM(4, false, false); }
     }
+#undef VQ_LAUNCH_GEMM
     return hipGetLastError();
 }
 

@@ -13,9 +13,10 @@ hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, i
 hipError_t launch_quantize_weight(const float* w, const float* chan_s, int w_bits, void* wq_out,
                                   float* w_scale, int N, int K, hipStream_t stream);
 
-// w_bits 8: w is int8 [N,K]; 4: w is packed nibbles [N,K/2].
+// w_bits 8: w is int8 [N,K]; 4: w is packed nibbles [N,K/2].  num_cus: compute units of
+// the device the stream belongs to (the kernel is persistent, one workgroup per CU).
 hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, int w_bits,
                        const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out,
-                       int M, int N, int K, hipStream_t stream);
+                       int M, int N, int K, int num_cus, hipStream_t stream);
 
 }  // namespace vq
