@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-seconds", type=float, default=15.0,
                    help="about how long the CPU oracle leg may run (it picks its token sample to fit)")
+    p.add_argument("--no-ceilings", action="store_true",
+                   help="skip the measured ceilings (register-only MFMA loop on realistic operands, copy kernel)")
     p.add_argument("--copy-calibration", action="store_true",
                    help="only run a plain 1 GiB device copy a few times (reference for the "
                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -71,6 +73,16 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the layer shards by tokens with no exchange; "
                  "nothing here uses a second device). Run with --gpus 1.")
+    ceilings = None
+    if not args.no_ceilings and not args.copy_calibration:
+        # a separate small program (csrc/vq_ceilings.hip), run as a child before this process touches the GPU
+        import subprocess
+        exe = os.path.join(ROOT, "paper_2406_02540_amd", "vq_ceilings")
+        if not os.path.exists(exe):
+            sys.exit("bench.py: %s not built (python -m paper_2406_02540_amd.build)" % exe)
+        ceilings = json.loads(subprocess.run([exe], check=True, capture_output=True, text=True, timeout=120).stdout)
+        log("measured ceilings:", ceilings)
+
     import numpy as np
     import torch
 
@@ -209,6 +221,13 @@ def main():
                           "(quantize + integer GEMM + dequantize), %.1f s" % (rows_big, dt))
         log(f"cpu oracle: {ops / dt / 1e9:.1f} GOP/s on {cpu['cores']} threads ({dt:.1f} s, {rows_big} tokens/layer)")
 
+    if ceilings:
+        roofline["measured_mfma_only_ceiling"] = ceilings["mfma_only_tops_activation_like_x_weight_like"]
+        roofline["frac_of_measured_ceiling"] = round(
+            g_achieved / ceilings["mfma_only_tops_activation_like_x_weight_like"], 4)
+        roofline_q["measured_copy_ceiling"] = ceilings["copy_1gib_read_plus_write_gbs"]
+        roofline_q["frac_of_measured_ceiling"] = round(q_achieved / ceilings["copy_1gib_read_plus_write_gbs"], 4)
+
     out = {
         "metric": "quantized-linear int8 TOPS (quant+GEMM+dequant)",
         "value": round(tops, 2),
@@ -228,6 +247,7 @@ def main():
         "roofline": roofline,
         "roofline_quantizer": roofline_q,
         "cpu_baseline": cpu,
+        "measured_ceilings": ceilings,
         "per_layer": [{k: (round(v, 2) if isinstance(v, float) else v) for k, v in p.items()} for p in per_layer],
     }
     print(json.dumps(out), flush=True)

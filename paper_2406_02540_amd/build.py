@@ -12,6 +12,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libvidiq.so")
+CEILINGS_PATH = os.path.join(PKG_DIR, "vq_ceilings")  # stand-alone program, see csrc/vq_ceilings.hip
 SOURCES = ["vq_api.hip", "vq_quantize.hip", "vq_gemm.hip"]
 
 HIPCC_FLAGS = [
@@ -56,6 +57,13 @@ def build(verbose: bool = True) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     os.replace(tmp, LIB_PATH)
+    # the ceilings probe (register-only MFMA loop, copy kernel): its own small executable
+    tmp = CEILINGS_PATH + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), *[f for f in HIPCC_FLAGS if f != "-fPIC"], os.path.join(CSRC, "vq_ceilings.hip"), "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, CEILINGS_PATH)
     return LIB_PATH
 
 

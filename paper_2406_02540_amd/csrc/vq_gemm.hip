@@ -355,7 +355,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 if (ks < 3) read_step(ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
-                if (fetch) issue_part(ld, buf ^ 1, fk0, ks);
+                // this wave's loads go out during the first two K steps: early enough to land
+                // before the stage ends, late enough not to queue up in front of its MFMAs
+                if (fetch && ks < 2) {
+                    issue_part(ld, buf ^ 1, fk0, 2 * ks);
+                    issue_part(ld, buf ^ 1, fk0, 2 * ks + 1);
+                }
                 // nothing moves across: the reads above stay ahead of the MFMAs below (the
                 // scheduler would otherwise sink them next to their uses to save registers)
                 __builtin_amdgcn_sched_barrier(0);
