@@ -275,7 +275,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     int buf = 0;  // LDS buffer of the stage about to be multiplied
 #pragma unroll
     for (int j = 0; j < 4; ++j) issue_part(ld, 0, 0, j);
+    wait_loads_and_barrier();  // the first tile's first stage (later ones arrive behind an epilogue)
 
+    // Invariant at the top of a stage: its operands have landed in buffer `buf` for every
+    // wave, and nobody reads or writes the other buffer any more.
     while (true) {
         const int next_idx = idx + a.slots;
         const bool has_next = tile_exists(next_idx);
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         const bool wave_live = (wave_c * 64 < cur.rows_w) && (wave_t * 128 < cur.rows_x);
 
         // Scales and bias of the tile: threads 0..255 fetch one channel and one token each
-        // here and park them in LDS after the mainloop, where every lane of the epilogue
+        // here and park them in LDS behind the last stage, where every lane of the epilogue
         // finds them.  Entries past N or M, and a missing bias, are zero.
         float pre_ws = 0.0f, pre_xs = 0.0f;
         _Float16 pre_b = (_Float16)0.0f;
@@ -298,6 +301,15 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             if (cur.tok0 + i < a.M) pre_xs = a.x_scale[cur.tok0 + i];
         }
 
+        auto park_scales = [&]() {
+            if (wave < 4) {
+                const int i = wave * 64 + opaque(lane);
+                *(float*)(lds_sc + i * 4) = pre_ws;
+                *(_Float16*)(lds_sc + 1024 + i * 2) = pre_b;
+                *(float*)(lds_sc + 2048 + i * 4) = pre_xs;
+            }
+        };
+
         v16i acc[2][4];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
@@ -307,10 +319,6 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                 for (int r = 0; r < 16; ++r) acc[cb][tb][r] = 0;
 
         for (int it = 0; it < nk; ++it) {
-            // Stage `it` has landed for every wave, and every wave is done with the other
-            // buffer (stage it-1, or the previous tile's epilogue staging), which the loads
-            // issued next overwrite.
-            wait_loads_and_barrier();
             // what to request while this stage is multiplied: the next stage of this tile,
             // or the first stage of the next tile
             const bool more = it + 1 < nk;
@@ -323,6 +331,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) issue_part(ld, buf ^ 1, fk0, j);
                 }
+                if (!more) park_scales();
+                wait_loads_and_barrier();
                 buf ^= 1;
                 continue;
             }
@@ -371,17 +381,15 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                         acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][cb], xf[ks & 1][tb],
                                                                             acc[cb][tb], 0, 0, 0);
             }
+            if (!more) park_scales();
+            // The stage requested above has landed for every wave and every wave is done
+            // reading this one.  After the last stage this also says: the scales are in LDS,
+            // the next tile's first stage is in, and only stores can be outstanding later.
+            wait_loads_and_barrier();
             buf ^= 1;
         }
-        // `buf` now names the buffer the next tile's first stage is landing in; the other
-        // one (the last stage multiplied) becomes the epilogue's staging area.
-        if (wave < 4) {
-            const int i = wave * 64 + opaque(lane);
-            *(float*)(lds_sc + i * 4) = pre_ws;
-            *(_Float16*)(lds_sc + 1024 + i * 2) = pre_b;
-            *(float*)(lds_sc + 2048 + i * 4) = pre_xs;
-        }
-        wait_lds_and_barrier();  // every wave is done reading the last stage; scales are visible
+        // `buf` now names the buffer that holds the next tile's first stage; the other one
+        // (the last stage multiplied) becomes the epilogue's staging area.
 
         // ---- epilogue ------------------------------------------------------------
         // Lane (h = lane/32, t = lane%32) holds, for each of its 4 token blocks, the
@@ -469,6 +477,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             }
         }
         if (!has_next) break;
+        // every wave has left its staging area: the next tile's second stage may land there
+        wait_lds_and_barrier();
         cur = nxt;
         idx = next_idx;
     }

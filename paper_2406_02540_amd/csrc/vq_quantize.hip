@@ -41,25 +41,30 @@ __device__ __forceinline__ int pack4(int a, int b, int c, int d) {
     return (a & 0xFF) | ((b & 0xFF) << 8) | ((c & 0xFF) << 16) | (d << 24);
 }
 
-// One wavefront per token.  Lane l owns the 16-byte chunks l, l+64, ... of the
-// row (8 fp16 each), so every load instruction of the wave covers one
-// contiguous 1 KiB piece of the row and every store 512 B.  NCH = chunks per
-// lane = ceil(K/8/64); the row stays in registers between the two passes.
-template <int NCH, bool HAS_MUL>
+// LANES (64, 32 or 16) lanes of a wavefront share a token, so a wavefront holds
+// 64 / LANES tokens.  Lane s of a token owns its 16-byte chunks s, s + LANES, ...
+// (8 fp16 each): every load instruction of the wave covers contiguous pieces of
+// 16 * LANES bytes and every store half of that.  NCH = chunks per lane; LANES is
+// chosen so that K / 8 = NCH * LANES exactly where possible (K = 1152: 16 lanes x
+// 9 chunks), which keeps every lane busy on every instruction.  The row stays in
+// registers as fp32 between the absmax pass and the quantizing pass.
+template <int NCH, int LANES, bool HAS_MUL>
 __global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave(
     const half8* __restrict__ x, const float4v* __restrict__ chan_mul, int2v* __restrict__ xq,
     float* __restrict__ x_scale, int M, int K8) {
+    constexpr int kRowsPerWave = kWave / LANES;
     const int lane = threadIdx.x & (kWave - 1);
-    const long m = (long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
-    if (m >= M) return;  // whole wavefront leaves together
-    const half8* row = x + m * K8;
+    const int sub = lane & (LANES - 1);
+    const long m = ((long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6)) * kRowsPerWave + lane / LANES;
+    const bool row_ok = m < M;  // lanes of a missing token idle but take part in the shuffles
+    const half8* row = x + (row_ok ? m : 0) * K8;
 
     float t[NCH][8];
     float amax = 0.0f;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-        const int c = i * kWave + lane;
-        if (c < K8) {
+        const int c = i * LANES + sub;
+        if (row_ok && c < K8) {
             const half8 v = __builtin_nontemporal_load(row + c);
 #pragma unroll
             for (int j = 0; j < 8; ++j) t[i][j] = (float)v[j];
@@ -78,20 +83,21 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave(
             for (int j = 0; j < 8; ++j) t[i][j] = 0.0f;
         }
     }
-    amax = wave_max(amax);
+#pragma unroll
+    for (int off = LANES / 2; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
 
     float scale = 0.0f, inv = 0.0f;
     if (amax != 0.0f) {
         scale = amax / 127.0f;
         inv = 127.0f / amax;
     }
-    if (lane == 0) x_scale[m] = scale;
+    if (row_ok && sub == 0) x_scale[m] = scale;
 
-    int2v* qrow = xq + m * K8;
+    int2v* qrow = xq + (row_ok ? m : 0) * K8;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-        const int c = i * kWave + lane;
-        if (c < K8) {
+        const int c = i * LANES + sub;
+        if (row_ok && c < K8) {
             int q[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) q[j] = quantize_one(t[i][j], inv, 127.0f);
@@ -190,17 +196,30 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_weight_rows(
     }
 }
 
-template <int NCH>
+template <int NCH, int LANES>
 hipError_t launch_wave(const void* x, const float* chan_mul, int8_t* xq, float* x_scale, int M,
                        int K, hipStream_t stream) {
-    const dim3 grid((unsigned)((M + kRowsPerBlock - 1) / kRowsPerBlock)), block(kQuantThreads);
+    constexpr int rows_per_block = kRowsPerBlock * (kWave / LANES);
+    const dim3 grid((unsigned)((M + rows_per_block - 1) / rows_per_block)), block(kQuantThreads);
     if (chan_mul)
-        hipLaunchKernelGGL((quantize_tokens_wave<NCH, true>), grid, block, 0, stream,
+        hipLaunchKernelGGL((quantize_tokens_wave<NCH, LANES, true>), grid, block, 0, stream,
                            (const half8*)x, (const float4v*)chan_mul, (int2v*)xq, x_scale, M, K / 8);
     else
-        hipLaunchKernelGGL((quantize_tokens_wave<NCH, false>), grid, block, 0, stream,
+        hipLaunchKernelGGL((quantize_tokens_wave<NCH, LANES, false>), grid, block, 0, stream,
                            (const half8*)x, (const float4v*)nullptr, (int2v*)xq, x_scale, M, K / 8);
     return hipGetLastError();
+}
+
+// NCH is a template parameter: pick the instantiation for the run-time chunk count.
+template <int LANES, int NCH = 1>
+hipError_t launch_wave_nch(int nch, const void* x, const float* chan_mul, int8_t* xq, float* x_scale,
+                           int M, int K, hipStream_t stream) {
+    if constexpr (NCH > 16) {
+        return hipErrorInvalidValue;
+    } else {
+        if (nch == NCH) return launch_wave<NCH, LANES>(x, chan_mul, xq, x_scale, M, K, stream);
+        return launch_wave_nch<LANES, NCH + 1>(nch, x, chan_mul, xq, x_scale, M, K, stream);
+    }
 }
 
 }  // namespace
@@ -212,22 +231,14 @@ hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, i
                      (((uintptr_t)x_f16 | (uintptr_t)xq) % 16 == 0) &&
                      (chan_mul == nullptr || (uintptr_t)chan_mul % 16 == 0);
     if (vec) {
-        const int nch = (K / 8 + kWave - 1) / kWave;
-        switch (nch) {
-            case 1: return launch_wave<1>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 2: return launch_wave<2>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 3: return launch_wave<3>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 4: return launch_wave<4>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 5: return launch_wave<5>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 6: return launch_wave<6>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 7:
-            case 8: return launch_wave<8>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 9: return launch_wave<9>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            case 10:
-            case 11:
-            case 12: return launch_wave<12>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-            default: return launch_wave<16>(x_f16, chan_mul, xq, x_scale, M, K, stream);
-        }
+        const int k8 = K / 8;
+        // the widest lane group that divides the row exactly; a whole wavefront otherwise
+        if (k8 % 64 == 0) return launch_wave_nch<64>(k8 / 64, x_f16, chan_mul, xq, x_scale, M, K, stream);
+        if (k8 % 32 == 0 && k8 / 32 <= 16)
+            return launch_wave_nch<32>(k8 / 32, x_f16, chan_mul, xq, x_scale, M, K, stream);
+        if (k8 % 16 == 0 && k8 / 16 <= 16)
+            return launch_wave_nch<16>(k8 / 16, x_f16, chan_mul, xq, x_scale, M, K, stream);
+        return launch_wave_nch<64>((k8 + 63) / 64, x_f16, chan_mul, xq, x_scale, M, K, stream);
     }
     const dim3 grid((unsigned)M), block(kQuantThreads);
     if (chan_mul)
