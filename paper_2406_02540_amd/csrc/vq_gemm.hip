@@ -48,17 +48,11 @@
 // The epilogue computes fp16_rne(fma_f32(float(acc) * x_scale, w_scale, bias)): one fp32
 // rounding fewer than three separate operations, so an output can differ from the
 // separately rounded value in the last fp16 place.
+#include "vq_gemm_common.h"
 #include "vq_internal.h"
 
 namespace vq {
 namespace {
-
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) void* lds_ptr;
 
 constexpr int kTileT = 256;                 // tokens per workgroup
 constexpr int kTileC = 256;                 // output channels per workgroup
@@ -73,7 +67,6 @@ constexpr int kScaleBytes = 3 * 1024;       // w_scale[256] fp32 | bias[256] fp1
 constexpr int kEpiWave = 64 * 128;          // a wavefront stages 64 tokens x 64 channels of fp16 at a time
 constexpr int kBand = 8;                    // token tiles per band in the tile order
 constexpr int kXcds = 8;
-constexpr unsigned kRsrcFlags = 0x00020000; // raw buffer, 32-bit data format
 static_assert(kWaves * kEpiWave == kXStage + kWStage, "epilogue staging is one stage buffer pair");
 
 struct GemmArgs {
@@ -88,79 +81,6 @@ struct GemmArgs {
     int tiles_t, tiles_c, tiles, tiles_per_xcd;
     int slots;  // workgroups per XCD; workgroup (xcd, slot) takes tiles slot, slot + slots, ... of its XCD
 };
-
-// LDS row r of the weight tile holds which output channel of the tile.
-// Rows are kept in MFMA order: r = slab*64 + b*32 + rho with rho = 8j + 4h + i
-// the row index inside MFMA block b; the accumulator register 4j + i of lanes
-// with lane/32 == h holds that row.  Sending channel slab*64 + 32h + 16b + 4j + i
-// there gives lane half h the 32 consecutive channels slab*64 + 32h .. +31.
-__device__ __forceinline__ int w_row_to_channel(int r) {
-    const int slab = r >> 6, b = (r >> 5) & 1, rho = r & 31;
-    const int j = rho >> 3, h = (rho >> 2) & 1, i = rho & 3;
-    return slab * 64 + 32 * h + 16 * b + 4 * j + i;
-}
-
-__device__ __forceinline__ unsigned clamp_u32(long v) {
-    return v > 0xFFFFFFFFl ? 0xFFFFFFFFu : (unsigned)v;
-}
-
-// Raw buffer descriptor: base address, no stride, size in bytes (accesses past
-// it read as zero and never fault), 32-bit data format.
-__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
-    const unsigned long long p = (unsigned long long)base;
-    v4i r;
-    r[0] = (int)(unsigned)p;
-    r[1] = (int)(unsigned)(p >> 32) & 0xFFFF;
-    r[2] = (int)bytes;
-    r[3] = (int)kRsrcFlags;
-    return r;
-}
-
-// 16 bytes per lane from buffer offset voff + soff straight into LDS at
-// lds_addr + 16 * lane (lds_addr is wave-uniform and goes through M0).  Counts
-// in vmcnt; the compiler does not know about it, see wait_loads_and_barrier().
-__device__ __forceinline__ void load_to_lds_16(v4i rsrc, unsigned lds_addr, int voff, int soff) {
-    asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "buffer_load_dwordx4 %1, %2, %3 offen lds"
-        :
-        : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-        : "memory");
-}
-
-// Waits until all of this wave's direct loads (and stores) have completed and all
-// its LDS accesses are done, then joins the workgroup barrier.
-__device__ __forceinline__ void wait_loads_and_barrier() {
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" : : : "memory");
-}
-
-// Barrier for LDS traffic only: loads in flight stay in flight.
-__device__ __forceinline__ void wait_lds_and_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory");
-}
-
-// 16 nibbles (two dwords) -> 16 bytes holding 16 * w: the nibble is moved to
-// the high half of its byte, sign bit included, in the order of K.
-__device__ __forceinline__ v4i widen_nibbles(v2i p) {
-    v4i o;
-#pragma unroll
-    for (int d = 0; d < 2; ++d) {
-        const unsigned w = (unsigned)p[d];
-        const unsigned even = (w << 4) & 0xF0F0F0F0u;  // k = 0,2,4,6 of this dword
-        const unsigned odd = w & 0xF0F0F0F0u;          // k = 1,3,5,7
-        o[2 * d] = (int)__builtin_amdgcn_perm(odd, even, 0x05010400u);      // k = 0,1,2,3
-        o[2 * d + 1] = (int)__builtin_amdgcn_perm(odd, even, 0x07030602u);  // k = 4,5,6,7
-    }
-    return o;
-}
-
-// Returns v unchanged but opaque to the optimiser: what is derived from the result is
-// recomputed where it is used instead of being kept in registers across the mainloop.
-__device__ __forceinline__ int opaque(int v) {
-    asm volatile("" : "+v"(v));
-    return v;
-}
 
 // Where a tile sits in the output (wave-uniform).
 struct TilePos {
@@ -504,6 +424,10 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     a.tiles_c = (N + kTileC - 1) / kTileC;
     const long tiles = (long)a.tiles_t * a.tiles_c;
     if (tiles > 0x7FFFFFF0l) return hipErrorInvalidValue;
+    // A problem whose large tiles would leave more than half of the CUs idle is latency
+    // bound: the small-tile kernel puts many more loads in flight.
+    if (tiles * 2 <= num_cus)
+        return launch_gemm_small(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, acc_out, M, N, K, stream);
     a.tiles = (int)tiles;
     a.tiles_per_xcd = (a.tiles + kXcds - 1) / kXcds;
     // one workgroup per CU (the kernel needs most of a CU's LDS), fewer if there are fewer tiles

@@ -19,4 +19,10 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
                        const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out,
                        int M, int N, int K, int num_cus, hipStream_t stream);
 
+// The small-tile kernel (64 x 64 tiles, deep load ring) that launch_gemm switches to when
+// the large tiles would occupy less than half of the CUs.
+hipError_t launch_gemm_small(const int8_t* xq, const float* x_scale, const void* w, int w_bits,
+                             const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out,
+                             int M, int N, int K, hipStream_t stream);
+
 }  // namespace vq
