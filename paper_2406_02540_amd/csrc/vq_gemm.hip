@@ -48,6 +48,8 @@
 // The epilogue computes fp16_rne(fma_f32(float(acc) * x_scale, w_scale, bias)): one fp32
 // rounding fewer than three separate operations, so an output can differ from the
 // separately rounded value in the last fp16 place.
+#include <type_traits>
+
 #include "vq_gemm_common.h"
 #include "vq_internal.h"
 
@@ -231,14 +233,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         };
 
         v16i acc[2][4];
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[cb][tb][r] = 0;
+        const v16i kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-        for (int it = 0; it < nk; ++it) {
+        // One stage.  FIRST (a compile-time flag): the tile's first stage, whose first K step
+        // starts the accumulators from zero (a constant operand, no registers to clear).
+        auto stage = [&](const int it, auto first_tag) {
+            constexpr bool FIRST = decltype(first_tag)::value;
             // what to request while this stage is multiplied: the next stage of this tile,
             // or the first stage of the next tile
             const bool more = it + 1 < nk;
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                 if (!more) park_scales();
                 wait_loads_and_barrier();
                 buf ^= 1;
-                continue;
+                return;
             }
 
             const int8_t* xs = lds_x + buf * kXStage;
@@ -297,9 +297,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-                    for (int tb = 0; tb < 4; ++tb)
-                        acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][cb], xf[ks & 1][tb],
-                                                                            acc[cb][tb], 0, 0, 0);
+                    for (int tb = 0; tb < 4; ++tb) {
+                        if (FIRST && ks == 0)
+                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[0][cb], xf[0][tb], kZero16, 0, 0, 0);
+                        else
+                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][cb], xf[ks & 1][tb],
+                                                                                acc[cb][tb], 0, 0, 0);
+                    }
             }
             if (!more) park_scales();
             // The stage requested above has landed for every wave and every wave is done
@@ -307,7 +311,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             // the next tile's first stage is in, and only stores can be outstanding later.
             wait_loads_and_barrier();
             buf ^= 1;
-        }
+        };
+        stage(0, std::true_type{});
+#pragma unroll 1
+        for (int it = 1; it < nk; ++it) stage(it, std::false_type{});
         // `buf` now names the buffer that holds the next tile's first stage; the other one
         // (the last stage multiplied) becomes the epilogue's staging area.
 
