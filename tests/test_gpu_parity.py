@@ -120,13 +120,23 @@ def _gemm_case(vq, oracle, M, N, K, bits, seed, bias=True, full_range=True):
     else:
         y, acc = vq.vq_gemm_w4a8(dev(xq), dev(xs), dev(oracle.pack_int4(wq)), dev(ws),
                                  None if b is None else dev(b), return_acc=True)
+    # the same call without the copy of the sums takes the kernel variant that stores whole lines
+    if bits == 8:
+        y_fast = vq.vq_gemm_w8a8(dev(xq), dev(xs), dev(wq), dev(ws), None if b is None else dev(b))
+    else:
+        y_fast = vq.vq_gemm_w4a8(dev(xq), dev(xs), dev(oracle.pack_int4(wq)), dev(ws),
+                                 None if b is None else dev(b))
     torch.cuda.synchronize()
     assert np.array_equal(host(acc), acc_ref), "int32 sums differ"
     worst = assert_fp16_close(host(y), y_ref, acc_ref, xs, ws, b)
+    assert torch.equal(y, y_fast), "outputs with and without acc_out differ"
     return worst, np.array_equal(host(y).view(np.uint16), y_ref.view(np.uint16))
 
 
-GEMM_SHAPES = [(1, 8, 16), (1, 8, 32), (33, 24, 96), (64, 128, 64), (256, 128, 128), (256, 1152, 1152),
+# The library picks its small-tile kernel when the 256 x 256 tiles would fill less than half of
+# the CUs and the persistent large-tile kernel otherwise; the last shapes are large enough for
+# the latter (>= 129 tiles on a 256-CU part) and ragged in M, N (also N % 8 != 0) and K.
+GEMM_SHAPES = [(2891, 2824, 144), (2891, 2820, 208), (2600, 3080, 128), (4099, 2056, 48), (1, 8, 16), (1, 8, 32), (33, 24, 96), (64, 128, 64), (256, 128, 128), (256, 1152, 1152),
                (300, 136, 224), (257, 264, 160), (513, 260, 64), (17, 7, 32), (240, 2304, 4096),
                (700, 392, 1184), (31, 129, 4608)]
 
