@@ -233,12 +233,18 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         };
 
         v16i acc[2][4];
+        v4i xf[2][4], wf[2][2];  // operand registers, double buffered; [1] carries K step 3 across stages
         const v16i kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-        // One stage.  FIRST (a compile-time flag): the tile's first stage, whose first K step
-        // starts the accumulators from zero (a constant operand, no registers to clear).
-        auto stage = [&](const int it, auto first_tag) {
+        // One stage = four K steps of 8 MFMAs per wave.  The schedule is skewed by one K step:
+        // the MFMAs of a stage's last K step are issued at the start of the next stage, behind
+        // the barrier, where they cover the latency of that stage's first LDS reads (otherwise
+        // every wave of the CU would sit idle there).  Compile-time flags: FIRST = the tile's
+        // first stage (nothing deferred to run; its first K step starts the accumulators from
+        // a constant zero), LAST = its last one (nothing is deferred past the epilogue).
+        auto stage = [&](const int it, auto first_tag, auto last_tag) __attribute__((always_inline)) {
             constexpr bool FIRST = decltype(first_tag)::value;
+            constexpr bool LAST = decltype(last_tag)::value;
             // what to request while this stage is multiplied: the next stage of this tile,
             // or the first stage of the next tile
             const bool more = it + 1 < nk;
@@ -246,23 +252,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             if (!more && has_next) decode_tile(next_idx, nxt, ld);
             const int fk0 = more ? (it + 1) * kTileK : 0;
 
-            if (!wave_live) {  // nothing to multiply, but this wave's share of the loads is needed
-                if (fetch) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) issue_part(ld, buf ^ 1, fk0, j);
-                }
-                if (!more) park_scales();
-                wait_loads_and_barrier();
-                buf ^= 1;
-                return;
-            }
-
             const int8_t* xs = lds_x + buf * kXStage;
             const int8_t* ws = lds_w + buf * kWStage;
             // Operand registers are double buffered: the LDS reads of K step ks+1 are
             // issued before the MFMAs of step ks, which cover their latency.
-            v4i xf[2][4], wf[2][2];
-            auto read_step = [&](int ks, v4i(&xo)[4], v4i(&wo)[2]) {
+            auto read_step = [&](int ks, v4i(&xo)[4], v4i(&wo)[2]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb) {
                     if (W_BITS == 8)
@@ -281,30 +275,44 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                     }
                 }
             };
-            read_step(0, xf[0], wf[0]);
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (ks < 3) read_step(ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
-                // this wave's loads go out during the first two K steps: early enough to land
-                // before the stage ends, late enough not to queue up in front of its MFMAs
-                if (fetch && ks < 2) {
-                    issue_part(ld, buf ^ 1, fk0, 2 * ks);
-                    issue_part(ld, buf ^ 1, fk0, 2 * ks + 1);
-                }
-                // nothing moves across: the reads above stay ahead of the MFMAs below (the
-                // scheduler would otherwise sink them next to their uses to save registers)
-                __builtin_amdgcn_sched_barrier(0);
+            auto mfma_step = [&](const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag) __attribute__((always_inline)) {
 #pragma unroll
                 for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
                     for (int tb = 0; tb < 4; ++tb) {
-                        if (FIRST && ks == 0)
-                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[0][cb], xf[0][tb], kZero16, 0, 0, 0);
+                        if constexpr (decltype(zero_tag)::value)
+                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], kZero16, 0, 0, 0);
                         else
-                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][cb], xf[ks & 1][tb],
-                                                                                acc[cb][tb], 0, 0, 0);
+                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], acc[cb][tb], 0, 0, 0);
                     }
+            };
+            constexpr std::false_type kAccumulate{};
+            // (sched_barrier: nothing moves across, so the LDS reads and loads stay ahead of the
+            // MFMAs that cover them; the scheduler would otherwise sink them next to their uses.)
+            read_step(0, xf[0], wf[0]);
+            if (fetch) {  // this wave's share of the next stage's loads, first half
+                issue_part(ld, buf ^ 1, fk0, 0);
+                issue_part(ld, buf ^ 1, fk0, 1);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            if (!FIRST) mfma_step(xf[1], wf[1], kAccumulate);  // K step 3 of the previous stage
+            __builtin_amdgcn_sched_barrier(0);
+            read_step(1, xf[1], wf[1]);
+            if (fetch) {  // second half
+                issue_part(ld, buf ^ 1, fk0, 2);
+                issue_part(ld, buf ^ 1, fk0, 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(xf[0], wf[0], first_tag);  // K step 0
+            __builtin_amdgcn_sched_barrier(0);
+            read_step(2, xf[0], wf[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(xf[1], wf[1], kAccumulate);  // K step 1
+            __builtin_amdgcn_sched_barrier(0);
+            read_step(3, xf[1], wf[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(xf[0], wf[0], kAccumulate);  // K step 2
+            if (LAST) mfma_step(xf[1], wf[1], kAccumulate);  // K step 3 (otherwise at the start of the next stage)
             if (!more) park_scales();
             // The stage requested above has landed for every wave and every wave is done
             // reading this one.  After the last stage this also says: the scales are in LDS,
@@ -312,9 +320,28 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             wait_loads_and_barrier();
             buf ^= 1;
         };
-        stage(0, std::true_type{});
+        if (!wave_live) {
+            // nothing to multiply in this tile, but this wave's share of the loads is needed
 #pragma unroll 1
-        for (int it = 1; it < nk; ++it) stage(it, std::false_type{});
+            for (int it = 0; it < nk; ++it) {
+                const bool more = it + 1 < nk;
+                if (!more && has_next) decode_tile(next_idx, nxt, ld);
+                if (more || has_next) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) issue_part(ld, buf ^ 1, more ? (it + 1) * kTileK : 0, j);
+                }
+                if (!more) park_scales();
+                wait_loads_and_barrier();
+                buf ^= 1;
+            }
+        } else if (nk == 1) {
+            stage(0, std::true_type{}, std::true_type{});
+        } else {
+            stage(0, std::true_type{}, std::false_type{});
+#pragma unroll 1
+            for (int it = 1; it < nk - 1; ++it) stage(it, std::false_type{}, std::false_type{});
+            stage(nk - 1, std::false_type{}, std::true_type{});
+        }
         // `buf` now names the buffer that holds the next tile's first stage; the other one
         // (the last stage multiplied) becomes the epilogue's staging area.
 
