@@ -287,31 +287,46 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                     }
             };
             constexpr std::false_type kAccumulate{};
-            // (sched_barrier: nothing moves across, so the LDS reads and loads stay ahead of the
-            // MFMAs that cover them; the scheduler would otherwise sink them next to their uses.)
-            read_step(0, xf[0], wf[0]);
+            // Inside a K step the six LDS reads of the next step are dealt out one behind each of
+            // the first six MFMAs (sched_group_barrier), so that a wave never leaves the matrix
+            // pipe without work while it issues a run of reads; sched_barrier(0) fences keep
+            // the steps apart (the scheduler would otherwise sink reads next to their uses).
+            auto interleave = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                for (int i = 0; i < 6; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            };
             if (fetch) {  // this wave's share of the next stage's loads, first half
                 issue_part(ld, buf ^ 1, fk0, 0);
                 issue_part(ld, buf ^ 1, fk0, 1);
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (!FIRST) mfma_step(xf[1], wf[1], kAccumulate);  // K step 3 of the previous stage
+            read_step(0, xf[0], wf[0]);
+            if (!FIRST) {
+                mfma_step(xf[1], wf[1], kAccumulate);  // K step 3 of the previous stage
+                if (W_BITS == 8) interleave();
+            }
             __builtin_amdgcn_sched_barrier(0);
-            read_step(1, xf[1], wf[1]);
             if (fetch) {  // second half
                 issue_part(ld, buf ^ 1, fk0, 2);
                 issue_part(ld, buf ^ 1, fk0, 3);
             }
             __builtin_amdgcn_sched_barrier(0);
+            read_step(1, xf[1], wf[1]);
             mfma_step(xf[0], wf[0], first_tag);  // K step 0
+            if (W_BITS == 8) interleave();
             __builtin_amdgcn_sched_barrier(0);
             read_step(2, xf[0], wf[0]);
-            __builtin_amdgcn_sched_barrier(0);
             mfma_step(xf[1], wf[1], kAccumulate);  // K step 1
+            if (W_BITS == 8) interleave();
             __builtin_amdgcn_sched_barrier(0);
             read_step(3, xf[1], wf[1]);
-            __builtin_amdgcn_sched_barrier(0);
             mfma_step(xf[0], wf[0], kAccumulate);  // K step 2
+            if (W_BITS == 8) interleave();
+            __builtin_amdgcn_sched_barrier(0);
             if (LAST) mfma_step(xf[1], wf[1], kAccumulate);  // K step 3 (otherwise at the start of the next stage)
             if (!more) park_scales();
             // The stage requested above has landed for every wave and every wave is done
