@@ -221,6 +221,14 @@ def main():
                           "(quantize + integer GEMM + dequantize), %.1f s" % (rows_big, dt))
         log(f"cpu oracle: {ops / dt / 1e9:.1f} GOP/s on {cpu['cores']} threads ({dt:.1f} s, {rows_big} tokens/layer)")
 
+    # HBM bytes per launch as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in separate runs of this
+    # same command (the counters cannot be read from inside a run); the summary names the commands.
+    traffic_file = os.path.join(ROOT, "profiles", "gemm_traffic_video_w8a8.json")
+    if args.workload == "video" and os.path.exists(traffic_file):
+        t = json.load(open(traffic_file))
+        roofline["traffic"] = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
+                               "algorithmic_bytes": int(sum(gemm_bytes(L["spec"]) for L, _ in big) / len(big)),
+                               "per": "launch, average over the %d large layers" % len(big), "source": t["source"]}
     if ceilings:
         roofline["measured_mfma_only_ceiling"] = ceilings["mfma_only_tops_activation_like_x_weight_like"]
         roofline["frac_of_measured_ceiling"] = round(
