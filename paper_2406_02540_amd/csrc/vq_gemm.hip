@@ -387,13 +387,26 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
 
             // staging: [64 token rows][128 B], 16-byte chunks XOR-ed by (row/2)%8; waves
             // 0..3 use the X buffer just consumed, waves 4..7 the W buffer.
-            int8_t* const stage = (wave < 4 ? lds_x + (buf ^ 1) * kXStage + wave * kEpiWave
-                                            : lds_w + (buf ^ 1) * kWStage + (wave - 4) * kEpiWave);
+            // (byte offsets into `lds`; the staging areas are 8 KiB aligned, so the XORs below
+            // stay inside the chunk bits)
+            const int stage = (wave < 4 ? (buf ^ 1) * kXStage + wave * kEpiWave
+                                        : kStages * kXStage + (buf ^ 1) * kWStage + (wave - 4) * kEpiWave);
+            // writes: this lane's token row (el%32, +32 for odd tb), logical chunk 4h+g
+            const int st_wr = stage + (el & 31) * 128 + ((4 * h ^ ((el >> 1) & 7)) << 4);
+            // flush reads: row 8i + el/8, logical chunk el%8 (its XOR mask alternates with i)
+            const int st_rd = stage + (el >> 3) * 128 + (((el & 7) ^ (el >> 4)) << 4);
+            // Flush stores are range-checked buffer stores relative to the tile's first token
+            // row: rows past M fall behind the end of the buffer, lanes whose channels lie past
+            // N get an offset behind it (N < 2^21 on this path, so nothing wraps).
+            const int cl = (int)chw + (el & 7) * 8;
+            const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
+                a.y + cur.tok0 * a.N, 0, (int)clamp_u32((long)cur.rows_x * a.N * 2), kRsrcFlags);
+            const unsigned y_off0 =
+                (cl < a.N) ? (unsigned)(((wave_t * 128 + (el >> 3)) * a.N + cl) * 2) : 0x80000000u;
 #pragma unroll
             for (int tb = 0; tb < 4; ++tb) {
                 const int tl = wave_t * 128 + tb * 32 + (el & 31);  // token within the tile
                 const float xsc = *(const float*)(lds_sc + 2048 + tl * 4);
-                const int srow = (tb & 1) * 32 + (el & 31);
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int b = g >> 1, r0 = (g & 1) * 8;
@@ -409,7 +422,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                         out[e] = (_Float16)y;
                     }
                     if (!GENERIC) {
-                        *(half8*)(stage + srow * 128 + (((4 * h + g) ^ ((srow >> 1) & 7)) << 4)) = out;
+                        *(half8*)(lds + (st_wr ^ (g << 4)) + (tb & 1) * 4096) = out;
                     } else if (tl < cur.rows_x) {
                         const long tok = cur.tok0 + tl;
                         const long c0 = chw + 32 * h + 8 * g;
@@ -431,15 +444,14 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                     // execute in order; the fences only keep the compiler from reordering them.
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
+                    v4i rows[8];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int row = i * 8 + (el >> 3);
-                        const half8 v = *(const half8*)(stage + row * 128 + (((el & 7) ^ ((row >> 1) & 7)) << 4));
-                        const int t = wave_t * 128 + (tb - 1) * 32 + row;
-                        const long c = chw + (el & 7) * 8;
-                        if (t < cur.rows_x && c < a.N)
-                            __builtin_nontemporal_store(v, (half8*)(a.y + (cur.tok0 + t) * a.N + c));
-                    }
+                    for (int i = 0; i < 8; ++i)
+                        rows[i] = *(const v4i*)(lds + (st_rd ^ ((i & 1) << 6)) + i * 1024);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            rows[i], rsrc_y, y_off0 + (unsigned)(((tb - 1) * 32 + i * 8) * a.N * 2), 0, 2 /* nontemporal */);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                 }
@@ -484,7 +496,7 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     a.slots = a.tiles_per_xcd < cus_per_xcd ? a.tiles_per_xcd : cus_per_xcd;
     const dim3 grid((unsigned)(a.slots * kXcds)), block(kThreads);
     const bool tail = (K % kTileK) != 0;
-    const bool generic = (N % 8) != 0 || acc_out != nullptr;
+    const bool generic = (N % 8) != 0 || acc_out != nullptr || N >= (1 << 21);
 #define VQ_LAUNCH_GEMM(BITS, TAIL, GEN) \
     hipLaunchKernelGGL((gemm_i8_dequant<BITS, TAIL, GEN>), grid, block, 0, stream, a)
     if (w_bits == 8) {
