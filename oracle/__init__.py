@@ -48,13 +48,19 @@ def _load():
         lib.oracle_float_to_half.restype = ctypes.c_uint16
         lib.oracle_float_to_half.argtypes = [ctypes.c_float]
         lib.oracle_quantize_per_token.argtypes = [p, p, p, p, i64, i64]
+        lib.oracle_quantize_rows_f32.argtypes = [p, p, p, p, i64, i64]
+        lib.oracle_gelu.argtypes = [p, ci, p, i64, i64]
+        lib.oracle_layernorm_modulate.argtypes = [p, p, p, i64, ctypes.c_double, p, i64, i64]
+        lib.oracle_residual.argtypes = [p, p, p, i64, p, i64, i64]
         lib.oracle_quantize_weight.argtypes = [p, p, ci, p, p, i64, i64]
         lib.oracle_pack_int4.argtypes = [p, p, i64, i64]
         lib.oracle_unpack_int4.argtypes = [p, p, i64, i64]
         lib.oracle_gemm_i8.argtypes = [p, p, p, i64, i64, i64]
         lib.oracle_dequant.argtypes = [p, p, p, p, p, i64, i64]
         lib.oracle_linear.argtypes = [p, p, p, ci, p, p, p, p, p, p, p, i64, i64, i64]
-        for name in ("oracle_quantize_per_token", "oracle_quantize_weight", "oracle_pack_int4",
+        for name in ("oracle_quantize_rows_f32", "oracle_gelu", "oracle_layernorm_modulate",
+                     "oracle_residual",
+                     "oracle_quantize_per_token", "oracle_quantize_weight", "oracle_pack_int4",
                      "oracle_unpack_int4", "oracle_gemm_i8", "oracle_dequant", "oracle_linear"):
             getattr(lib, name).restype = ci
         _lib = lib
@@ -109,6 +115,84 @@ def quantize_per_token(x_f16, chan_mul=None):
     _check(_load().oracle_quantize_per_token(_ptr(xb), _ptr(cm), _ptr(xq), _ptr(xs), M, K),
            "quantize_per_token")
     return xq, xs
+
+
+def quantize_rows_f32(t_f32, chan_mul=None):
+    """The quantizer steps on rows that already are fp32: t [M,K] -> (xq, x_scale)."""
+    t = _arr(t_f32, np.float32)
+    M, K = t.shape
+    cm = None if chan_mul is None else _arr(chan_mul, np.float32, (K,))
+    xq = np.empty((M, K), np.int8)
+    xs = np.empty((M,), np.float32)
+    _check(_load().oracle_quantize_rows_f32(_ptr(t), _ptr(cm), _ptr(xq), _ptr(xs), M, K),
+           "quantize_rows_f32")
+    return xq, xs
+
+
+def gelu(h_f16, approximate: bool = False):
+    """GELU of fp16 [M,K] (exact, or the tanh form), evaluated in fp64 -> fp32 [M,K]."""
+    hb = _f16(h_f16)
+    M, K = hb.shape
+    t = np.empty((M, K), np.float32)
+    _check(_load().oracle_gelu(_ptr(hb), int(bool(approximate)), _ptr(t), M, K), "gelu")
+    return t
+
+
+def _per_sample(a, M, K, tokens_per_sample, what):
+    if a is None:
+        return None
+    B = (M + tokens_per_sample - 1) // tokens_per_sample
+    a = _arr(a, np.float32)
+    if a.shape != (B, K):
+        raise ValueError(f"{what}: expected shape {(B, K)}, got {a.shape}")
+    return a
+
+
+def layernorm_modulate(x_f16, scale=None, shift=None, tokens_per_sample=None, eps: float = 1e-6):
+    """LayerNorm over the channels of each token, then (1 + scale[b]) * y + shift[b] with
+    b = m // tokens_per_sample; fp64 -> fp32 [M,K]."""
+    xb = _f16(x_f16)
+    M, K = xb.shape
+    T = int(tokens_per_sample) if tokens_per_sample else max(M, 1)
+    sc = _per_sample(scale, M, K, T, "scale")
+    sh = _per_sample(shift, M, K, T, "shift")
+    t = np.empty((M, K), np.float32)
+    _check(_load().oracle_layernorm_modulate(_ptr(xb), _ptr(sc), _ptr(sh), T, float(eps), _ptr(t), M, K),
+           "layernorm_modulate")
+    return t
+
+
+def residual(x_f16, y_f16, gate=None, tokens_per_sample=None):
+    """r = x + gate[b] * y in fp32 (product and sum rounded), narrowed to fp16 [M,K]."""
+    xb = _f16(x_f16)
+    yb = _f16(y_f16)
+    if xb.shape != yb.shape:
+        raise ValueError("x and y differ in shape")
+    M, K = xb.shape
+    T = int(tokens_per_sample) if tokens_per_sample else max(M, 1)
+    g = _per_sample(gate, M, K, T, "gate")
+    r = np.empty((M, K), np.uint16)
+    _check(_load().oracle_residual(_ptr(xb), _ptr(yb), _ptr(g), T, _ptr(r), M, K), "residual")
+    return r.view(np.float16)
+
+
+def gelu_quantize(h_f16, chan_mul=None, approximate: bool = False):
+    """GELU fused with the quantizer: returns (t fp32, xq, x_scale)."""
+    t = gelu(h_f16, approximate)
+    return (t,) + quantize_rows_f32(t, chan_mul)
+
+
+def layernorm_quantize(x_f16, scale=None, shift=None, tokens_per_sample=None, eps: float = 1e-6,
+                       chan_mul=None):
+    """LayerNorm + modulation fused with the quantizer: returns (t fp32, xq, x_scale)."""
+    t = layernorm_modulate(x_f16, scale, shift, tokens_per_sample, eps)
+    return (t,) + quantize_rows_f32(t, chan_mul)
+
+
+def residual_quantize(x_f16, y_f16, gate=None, tokens_per_sample=None, chan_mul=None):
+    """Residual add fused with the quantizer: returns (r fp16, xq, x_scale)."""
+    r = residual(x_f16, y_f16, gate, tokens_per_sample)
+    return (r,) + quantize_per_token(r, chan_mul)
 
 
 def quantize_weight(w_f32, chan_s=None, bits: int = 8):

@@ -35,6 +35,18 @@
  *   - the integer sum is taken in int64 and must fit int32.
  *   - y = fp16_rne( ((float)acc * x_scale[m]) * w_scale[n] + float(bias[n]) ).
  *
+ *   - producers fused with the quantizer (Sec. 5.1 "Hardware Implementation
+ *     Settings": the quantization is integrated into the preceding LayerNorm,
+ *     GELU and residual operations).  The paper gives no formulas for them, so
+ *     the textbook ones are used: LayerNorm over the channels of a token with
+ *     the biased variance, followed by the DiT feature modulation
+ *     (1 + scale) * y + shift of the token's sample; GELU x Phi(x), exactly or
+ *     in its tanh form; residual r = x + gate * y.  LayerNorm and GELU are
+ *     evaluated in fp64 and rounded once to fp32, and that fp32 row is quantized
+ *     with the steps above; the residual is fp32 (one multiply, one add, each
+ *     rounded), narrowed to fp16 as the new residual stream, and that fp16 row is
+ *     quantized.
+ *
  * Matrices are dense row-major: X[M,K], W[N,K] (K contiguous), Y[M,N].
  * fp16 values travel as uint16_t bit patterns.
  *
@@ -42,10 +54,15 @@
  * (hand examples, closed-form error bounds, symmetries, brute-force sums,
  * numpy's own float16 conversion); none is "parity unpinned".
  */
+#define _USE_MATH_DEFINES
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
 #include <string.h>
+
+#ifndef M_PI
+#define M_PI 3.14159265358979323846
+#endif
 
 #define ORACLE_OK 0
 #define ORACLE_ERR_ARG 1
@@ -127,6 +144,117 @@ int oracle_quantize_per_token(const uint16_t* x_f16, const float* chan_mul,
             if (q > 127.0f) q = 127.0f;
             if (q < -127.0f) q = -127.0f;
             xq[m * K + k] = (int8_t)q;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ---- producers fused with the quantizer (Sec. 5.1, hardware implementation) ----
+ * A fused kernel never writes the producer's output: it quantizes it in
+ * registers.  Here each producer is a function of its own that writes the row
+ * it would hand to the quantizer, so that a test can look at it.              */
+
+/* The quantizer steps of oracle_quantize_per_token on a row that already is fp32. */
+int oracle_quantize_rows_f32(const float* t_f32, const float* chan_mul,
+                             int8_t* xq, float* x_scale, int64_t M, int64_t K) {
+    if (!t_f32 || !xq || !x_scale || M < 0 || K <= 0) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float* row = t_f32 + m * K;
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = row[k];
+            if (chan_mul) t = t * chan_mul[k];
+            float a = fabsf(t);
+            if (a > amax) amax = a;
+        }
+        float scale = 0.0f, inv = 0.0f;
+        if (amax != 0.0f) {
+            scale = amax / 127.0f;
+            inv = 127.0f / amax;
+        }
+        x_scale[m] = scale;
+        for (int64_t k = 0; k < K; ++k) {
+            float t = row[k];
+            if (chan_mul) t = t * chan_mul[k];
+            float q = rintf(t * inv);
+            if (q > 127.0f) q = 127.0f;
+            if (q < -127.0f) q = -127.0f;
+            xq[m * K + k] = (int8_t)q;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* GELU(x) = x * Phi(x) with Phi the standard normal distribution function.
+ * approximate == 0: Phi(x) = (1 + erf(x / sqrt 2)) / 2.
+ * approximate == 1: the tanh form, Phi(x) ~ (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) / 2.
+ * fp64 throughout, one rounding to fp32 at the end.                            */
+int oracle_gelu(const uint16_t* h_f16, int approximate, float* t_f32, int64_t M, int64_t K) {
+    if (!h_f16 || !t_f32 || M < 0 || K <= 0 || (approximate != 0 && approximate != 1))
+        return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M * K; ++i) {
+        const double x = (double)oracle_half_to_float(h_f16[i]);
+        double phi;
+        if (approximate == 0)
+            phi = 0.5 * (1.0 + erf(x / sqrt(2.0)));
+        else
+            phi = 0.5 * (1.0 + tanh(sqrt(2.0 / M_PI) * (x + 0.044715 * x * x * x)));
+        t_f32[i] = (float)(x * phi);
+    }
+    return ORACLE_OK;
+}
+
+/* LayerNorm of every token over its K channels (mean and biased variance of the
+ * token, eps inside the square root, no learned affine), then the modulation of
+ * the token's sample b = m / tokens_per_sample: (1 + scale[b,k]) * y + shift[b,k].
+ * scale and shift are fp32 [ceil(M / tokens_per_sample), K]; either may be NULL
+ * (no scaling, no shift).  fp64 throughout, one rounding to fp32 at the end.    */
+int oracle_layernorm_modulate(const uint16_t* x_f16, const float* scale, const float* shift,
+                              int64_t tokens_per_sample, double eps, float* t_f32,
+                              int64_t M, int64_t K) {
+    if (!x_f16 || !t_f32 || M < 0 || K <= 0 || tokens_per_sample <= 0 || !(eps >= 0.0))
+        return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t* row = x_f16 + m * K;
+        const int64_t b = m / tokens_per_sample;
+        double mean = 0.0;
+        for (int64_t k = 0; k < K; ++k) mean += (double)oracle_half_to_float(row[k]);
+        mean /= (double)K;
+        double var = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            const double d = (double)oracle_half_to_float(row[k]) - mean;
+            var += d * d;
+        }
+        var /= (double)K;
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int64_t k = 0; k < K; ++k) {
+            double y = ((double)oracle_half_to_float(row[k]) - mean) * rstd;
+            if (scale) y = y * (1.0 + (double)scale[b * K + k]);
+            if (shift) y = y + (double)shift[b * K + k];
+            t_f32[m * K + k] = (float)y;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* Residual connection r = x + gate * y with the gate of the token's sample
+ * (fp32 [ceil(M / tokens_per_sample), K], NULL for 1): fp32, the product rounded,
+ * then the sum rounded, then narrowed to fp16 -- the new residual stream.       */
+int oracle_residual(const uint16_t* x_f16, const uint16_t* y_f16, const float* gate,
+                    int64_t tokens_per_sample, uint16_t* r_f16, int64_t M, int64_t K) {
+    if (!x_f16 || !y_f16 || !r_f16 || M < 0 || K <= 0 || tokens_per_sample <= 0)
+        return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const int64_t b = m / tokens_per_sample;
+        for (int64_t k = 0; k < K; ++k) {
+            float p = oracle_half_to_float(y_f16[m * K + k]);
+            if (gate) p = gate[b * K + k] * p;
+            const float r = oracle_half_to_float(x_f16[m * K + k]) + p;
+            r_f16[m * K + k] = oracle_float_to_half(r);
         }
     }
     return ORACLE_OK;

@@ -1,0 +1,196 @@
+"""Pins the oracle's producer functions (GELU, LayerNorm + modulation, residual add:
+the operations the quantizer is fused into, Sec. 5.1 "Hardware Implementation
+Settings") to things other than themselves: library routines that compute the same
+textbook function by another route (scipy's normal distribution function, torch's
+float64 gelu and layer_norm, numpy's float32/float16 arithmetic), closed forms,
+symmetries and hand-worked roundings.
+"""
+import numpy as np
+import pytest
+import torch
+from scipy.special import ndtr
+
+
+def _f16_grid():
+    """Every finite fp16 value of magnitude at most 12 (GELU is x or 0 beyond)."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    v = bits.view(np.float16)
+    keep = np.isfinite(v) & (np.abs(v.astype(np.float32)) <= 12.0)
+    return v[keep].reshape(1, -1)
+
+
+# ---- GELU -------------------------------------------------------------------------
+
+def test_gelu_exact_is_x_times_normal_cdf(oracle):
+    x = _f16_grid()
+    want = x.astype(np.float64) * ndtr(x.astype(np.float64))  # scipy's Phi, not erf
+    got = oracle.gelu(x, approximate=False).astype(np.float64)
+    assert np.all(np.abs(got - want) <= 1e-7 * np.abs(want) + 1e-12 + np.abs(np.spacing(want.astype(np.float32))))
+
+
+def test_gelu_known_values(oracle):
+    # Phi(1) = 0.841344746068543, Phi(2) = 0.977249868051821 (standard normal table)
+    x = np.array([[0.0, 1.0, -1.0, 2.0, -2.0]], np.float16)
+    got = oracle.gelu(x, approximate=False)[0].astype(np.float64)
+    want = np.array([0.0, 0.841344746068543, -0.158655253931457, 1.954499736103642, -0.045500263896358])
+    assert np.allclose(got, want, rtol=2e-7, atol=1e-9)
+
+
+def test_gelu_tanh_form_against_torch(oracle):
+    x = _f16_grid()
+    want = torch.nn.functional.gelu(torch.from_numpy(x.astype(np.float64)), approximate="tanh").numpy()
+    got = oracle.gelu(x, approximate=True).astype(np.float64)
+    assert np.all(np.abs(got - want) <= np.abs(np.spacing(want.astype(np.float32))) + 1e-12)
+    # and the two forms differ by what the approximation is known for (< 5e-4 absolute), not more
+    exact = oracle.gelu(x, approximate=False).astype(np.float64)
+    d = np.abs(got - exact).max()
+    assert 1e-5 < d < 5e-4
+
+
+@pytest.mark.parametrize("approximate", [False, True])
+def test_gelu_odd_part_is_half_x(oracle, approximate):
+    # x Phi(x) - (-x) Phi(-x) = x (Phi(x) + Phi(-x)) = x, for both forms (tanh is odd)
+    x = _f16_grid()
+    pos = oracle.gelu(x, approximate).astype(np.float64)
+    neg = oracle.gelu((-x).astype(np.float16), approximate).astype(np.float64)
+    xf = x.astype(np.float64)
+    assert np.all(np.abs((pos - neg) - xf) <= 2.5e-7 * np.abs(xf) + 1e-12)
+
+
+@pytest.mark.parametrize("approximate", [False, True])
+def test_gelu_tails(oracle, approximate):
+    x = np.array([[8.0, 10.0, 100.0, 60000.0, -8.0, -10.0, -100.0, -60000.0]], np.float16)
+    got = oracle.gelu(x, approximate)[0]
+    assert np.array_equal(got[:4], x[0, :4].astype(np.float32))
+    assert np.all(np.abs(got[4:]) < 1e-13) and not np.isnan(got).any()
+
+
+# ---- LayerNorm + modulation -------------------------------------------------------
+
+def test_layernorm_against_torch_float64(oracle):
+    g = np.random.default_rng(11)
+    for K in (8, 100, 1152):
+        x = (g.standard_normal((9, K)) * g.uniform(0.1, 30, (9, 1)) + g.uniform(-5, 5, (9, 1))).astype(np.float16)
+        want = torch.nn.functional.layer_norm(torch.from_numpy(x.astype(np.float64)), (K,), eps=1e-6).numpy()
+        got = oracle.layernorm_modulate(x, eps=1e-6).astype(np.float64)
+        assert np.all(np.abs(got - want) <= np.abs(np.spacing(want.astype(np.float32))) + 1e-12)
+
+
+def test_layernorm_closed_forms(oracle):
+    K = 64
+    # +-a alternating: mean 0, variance a^2
+    a = 3.0
+    x = np.tile(np.array([a, -a], np.float16), K // 2)[None, :]
+    got = oracle.layernorm_modulate(x, eps=1e-6)[0].astype(np.float64)
+    assert np.allclose(got, x[0].astype(np.float64) / np.sqrt(a * a + 1e-6), rtol=1e-7)
+    # 0, 1, ..., K-1: mean (K-1)/2, variance (K^2-1)/12
+    x = np.arange(K, dtype=np.float16)[None, :]
+    got = oracle.layernorm_modulate(x, eps=0.0)[0].astype(np.float64)
+    want = (np.arange(K) - (K - 1) / 2) / np.sqrt((K * K - 1) / 12)
+    assert np.allclose(got, want, rtol=1e-7, atol=1e-9)
+    # a constant token has nothing to normalise: zeros, and the shift alone after modulation
+    x = np.full((1, K), 7.0, np.float16)
+    assert np.array_equal(oracle.layernorm_modulate(x, eps=1e-6), np.zeros((1, K), np.float32))
+    sh = np.linspace(-1, 1, K, dtype=np.float32)[None, :]
+    assert np.array_equal(oracle.layernorm_modulate(x, shift=sh, eps=1e-6), sh)
+
+
+def test_layernorm_invariances(oracle):
+    g = np.random.default_rng(12)
+    x = g.integers(-40, 40, (5, 96)).astype(np.float16)
+    base = oracle.layernorm_modulate(x, eps=0.0)
+    # a shift of the whole token and a positive scaling leave it unchanged (eps = 0);
+    # integers keep the fp16 inputs exact
+    assert np.allclose(oracle.layernorm_modulate((x + 17).astype(np.float16), eps=0.0), base, rtol=0, atol=1e-6)
+    assert np.allclose(oracle.layernorm_modulate((x * 4).astype(np.float16), eps=0.0), base, rtol=0, atol=1e-6)
+    assert np.allclose(oracle.layernorm_modulate((-x).astype(np.float16), eps=0.0), -base, rtol=0, atol=1e-6)
+    # what it returns has mean 0 and mean square var / (var + eps)
+    t = oracle.layernorm_modulate(x, eps=1e-2).astype(np.float64)
+    var = x.astype(np.float64).var(axis=1)
+    assert np.allclose(t.mean(axis=1), 0, atol=1e-7)
+    assert np.allclose((t * t).mean(axis=1), var / (var + 1e-2), rtol=1e-6)
+
+
+def test_modulation_uses_the_sample_of_the_token(oracle):
+    g = np.random.default_rng(13)
+    M, K, T = 7, 32, 3  # samples of 3, 3 and 1 tokens
+    x = g.standard_normal((M, K)).astype(np.float16)
+    sc = g.standard_normal((3, K)).astype(np.float32)
+    sh = g.standard_normal((3, K)).astype(np.float32)
+    y = oracle.layernorm_modulate(x, eps=1e-6).astype(np.float64)
+    got = oracle.layernorm_modulate(x, sc, sh, tokens_per_sample=T, eps=1e-6).astype(np.float64)
+    b = np.arange(M) // T
+    want = y * (1.0 + sc[b].astype(np.float64)) + sh[b].astype(np.float64)
+    assert np.allclose(got, want, rtol=3e-7, atol=3e-7)
+    # scale = -1 removes the token: the shift alone is left, exactly
+    got = oracle.layernorm_modulate(x, -np.ones((3, K), np.float32), sh, tokens_per_sample=T)
+    assert np.array_equal(got, sh[b])
+    with pytest.raises(ValueError):
+        oracle.layernorm_modulate(x, sc[:2], sh, tokens_per_sample=T)
+
+
+# ---- residual add ------------------------------------------------------------------
+
+def test_residual_hand_roundings(oracle):
+    # fp16 has steps of 2 from 2048 on: 2049 -> 2048 (down), 2051 is a tie -> 2052 (even), 2053 -> 2052
+    x = np.array([[2048, 2048, 2048, 1.0, 1.0]], np.float16)
+    y = np.array([[1, 3, 5, 0.5, 3.0]], np.float16)
+    assert oracle.residual(x, y)[0].tolist() == [2048.0, 2052.0, 2052.0, 1.5, 4.0]
+    # gate 0.5: 1 + 0.25 = 1.25; gate fl(1/3) * 3 rounds to exactly 1 in fp32, so 1 + 1 = 2
+    gate = np.array([[0.5, 0.5, 0.5, 0.5, np.float32(1.0) / np.float32(3.0)]], np.float32)
+    got = oracle.residual(x, y, gate)[0].tolist()
+    assert got == [2048.0, 2050.0, 2050.0, 1.25, 2.0]  # 2049.5 -> 2050, 2050.5 -> 2050
+
+
+def test_residual_against_numpy_float32(oracle):
+    g = np.random.default_rng(14)
+    M, K, T = 10, 200, 4
+    x = (g.standard_normal((M, K)) * 50).astype(np.float16)
+    y = (g.standard_normal((M, K)) * 3).astype(np.float16)
+    gate = g.standard_normal((3, K)).astype(np.float32)
+    b = np.arange(M) // T
+    want = (x.astype(np.float32) + gate[b] * y.astype(np.float32)).astype(np.float16)  # numpy rounds each step
+    assert np.array_equal(oracle.residual(x, y, gate, tokens_per_sample=T).view(np.uint16), want.view(np.uint16))
+    want = (x.astype(np.float32) + y.astype(np.float32)).astype(np.float16)
+    assert np.array_equal(oracle.residual(x, y).view(np.uint16), want.view(np.uint16))
+
+
+# ---- the quantizer on fp32 rows, and the three fused front ends --------------------
+
+def test_quantize_rows_f32_reduces_to_the_fp16_quantizer(oracle):
+    g = np.random.default_rng(15)
+    x = (g.standard_normal((12, 160)) * g.uniform(0.01, 100, (12, 1))).astype(np.float16)
+    x[3] = 0
+    cm = np.exp(g.uniform(np.log(0.25), np.log(4), 160)).astype(np.float32)
+    for mul in (None, cm):
+        q16, s16 = oracle.quantize_per_token(x, mul)
+        q32, s32 = oracle.quantize_rows_f32(x.astype(np.float32), mul)
+        assert np.array_equal(q16, q32) and np.array_equal(s16.view(np.uint32), s32.view(np.uint32))
+
+
+def test_quantize_rows_f32_error_bound_on_fp32_rows(oracle):
+    g = np.random.default_rng(16)
+    t = (g.standard_normal((20, 333)) * g.uniform(1e-3, 1e3, (20, 1))).astype(np.float32)
+    q, s = oracle.quantize_rows_f32(t)
+    err = np.abs(q.astype(np.float64) * s[:, None].astype(np.float64) - t.astype(np.float64))
+    assert np.all(err <= 0.5 * s[:, None].astype(np.float64) * (1 + 2.0 ** -15))
+    assert np.all(np.abs(q).max(axis=1) == 127)
+
+
+def test_fused_front_ends_compose_the_pinned_parts(oracle):
+    g = np.random.default_rng(17)
+    M, K, T = 6, 64, 3
+    x = g.standard_normal((M, K)).astype(np.float16)
+    y = g.standard_normal((M, K)).astype(np.float16)
+    cm = np.exp(g.uniform(-1, 1, K)).astype(np.float32)
+    sc = g.standard_normal((2, K)).astype(np.float32)
+    t, q, s = oracle.gelu_quantize(x, cm, approximate=True)
+    assert np.array_equal(t, oracle.gelu(x, True))
+    q2, s2 = oracle.quantize_rows_f32(t, cm)
+    assert np.array_equal(q, q2) and np.array_equal(s, s2)
+    t, q, s = oracle.layernorm_quantize(x, sc, None, T, 1e-6, cm)
+    assert np.array_equal(t, oracle.layernorm_modulate(x, sc, None, T, 1e-6))
+    r, q, s = oracle.residual_quantize(x, y, sc, T, cm)
+    assert np.array_equal(r.view(np.uint16), oracle.residual(x, y, sc, T).view(np.uint16))
+    q2, s2 = oracle.quantize_per_token(r, cm)
+    assert np.array_equal(q, q2) and np.array_equal(s, s2)
