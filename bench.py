@@ -41,6 +41,8 @@ def parse():
                    help="about how long the CPU oracle leg may run (it picks its token sample to fit)")
     p.add_argument("--no-ceilings", action="store_true",
                    help="skip the measured ceilings (register-only MFMA loop on realistic operands, copy kernel)")
+    p.add_argument("--no-fused", action="store_true",
+                   help="skip the timings of the quantizer fused behind LayerNorm / GELU / residual add")
     p.add_argument("--copy-calibration", action="store_true",
                    help="only run a plain 1 GiB device copy a few times (reference for the "
                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -190,6 +192,39 @@ def main():
                       peak=HBM_PEAK_GBS, unit="GB/s", frac=round(q_achieved / HBM_PEAK_GBS, 4), traffic=None,
                       launches="the %d quantizer launches with M >= 1024, bytes = 3MK + 4M (+4K) each" % len(big))
 
+    # ---- the quantizer fused behind its producer, on the same activations ----------------------
+    # (not part of the step: LayerNorm + modulation feeds qkv and fc1, GELU feeds fc2, the residual
+    # add feeds the next block; bytes = what such a kernel must move, 3MK + 4M, residual 7MK + 4M)
+    fused = []
+    if not args.no_fused:
+        g = torch.Generator(device="cuda").manual_seed(wl.SEED)
+        for L in layers:
+            s = L["spec"]
+            if s.M < 1024 or s.K > 8192 or s.K % 8:
+                continue
+            mod = [torch.randn((2, s.K), generator=g, device="cuda") * 0.3 for _ in range(2)]
+            T = (s.M + 1) // 2
+            if s.name == "fc2":
+                runs = [("gelu_tanh_quantize", 3, lambda: vq.vq_gelu_quantize(L["x"], True, L["cm"], xq=L["xq"], x_scale=L["xs"]))]
+            elif s.name == "proj":
+                r = torch.empty_like(L["x"])
+                yb = (L["x"].float() * 0.25).half()
+                runs = [("residual_quantize", 7, lambda: vq.vq_residual_quantize(L["x"], yb, mod[0], T, r, L["cm"], xq=L["xq"], x_scale=L["xs"]))]
+            else:
+                runs = [("layernorm_quantize", 3, lambda: vq.vq_layernorm_quantize(L["x"], mod[0], mod[1], T, 1e-6, L["cm"], xq=L["xq"], x_scale=L["xs"]))]
+            for name, bpe, fn in runs:
+                for _ in range(2):
+                    fn()
+                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nrep)]
+                for a, b in evs:
+                    a.record(); fn(); b.record()
+                torch.cuda.synchronize()
+                dt = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+                nbytes = bpe * s.M * s.K + 4 * s.M
+                fused.append(dict(kernel=name, feeds=s.name, M=s.M, K=s.K, us=round(dt * 1e6, 2),
+                                  GBps=round(nbytes / dt / 1e9, 1), frac_of_hbm_peak=round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4)))
+                log(f"fused {name:20s} -> {s.name:4s} {s.M}x{s.K}: {dt * 1e6:7.1f} us  {nbytes / dt / 1e9:6.0f} GB/s")
+
     # ---- the CPU oracle timed beside it, on a bounded sample of the same workload ---------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -255,6 +290,7 @@ def main():
         "roofline": roofline,
         "roofline_quantizer": roofline_q,
         "cpu_baseline": cpu,
+        "fused_quantizers": fused,
         "measured_ceilings": ceilings,
         "per_layer": [{k: (round(v, 2) if isinstance(v, float) else v) for k, v in p.items()} for p in per_layer],
     }

@@ -51,6 +51,7 @@ typedef enum vq_status {
 } vq_status;
 
 #define VQ_MAX_K 131072
+#define VQ_MAX_FUSED_K 8192 /* the fused quantizers keep a token in registers */
 
 /*
  * Dynamic per-token activation quantizer (Sec. 4.1 "Fine-grained Grouping and
@@ -71,6 +72,42 @@ typedef enum vq_status {
  */
 int vq_quantize_per_token(const void* x_f16, const float* chan_mul, int8_t* xq, float* x_scale,
                           int M, int K, void* hip_stream);
+
+/*
+ * The same quantizer fused behind the operation that produces its input (Sec. 5.1
+ * "Hardware Implementation Settings": the quantization is integrated into the
+ * preceding LayerNorm, GELU and residual operations; Sec. 4.1: the dynamic
+ * parameters only need the extrema of the token and can be fused with the previous
+ * operation).  The producer's fp32 result t[m,k] takes the place of float(x[m,k]) in
+ * vq_quantize_per_token and is never written to memory.  The paper gives no formulas
+ * for the producers; the textbook ones are used.  All three need K % 8 == 0 and
+ * K <= VQ_MAX_FUSED_K (VQ_ERR_SHAPE otherwise) and 16-byte aligned pointers.
+ * "Sample" b of token m is m / tokens_per_sample (the images or videos of a batch,
+ * e.g. the two halves of a classifier-free-guidance pair); per-sample arrays are fp32
+ * [ceil(M / tokens_per_sample), K].  chan_mul, xq, x_scale, M, K, hip_stream: as above.
+ *
+ * vq_gelu_quantize:       t = GELU(float(h[m,k])) = x Phi(x); approximate = 0 evaluates
+ *                         Phi with erf, 1 uses the tanh form
+ *                         Phi(x) ~ (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) / 2.
+ * vq_layernorm_quantize:  y = (x - mean) / sqrt(var + eps) over the K channels of the
+ *                         token (biased variance, no learned affine), then the feature
+ *                         modulation t = (1 + mod_scale[b,k]) y + mod_shift[b,k]; either
+ *                         array may be NULL (no scaling / no shift).
+ * vq_residual_quantize:   r = x + gate[b,k] * y (gate NULL = 1), product and sum each
+ *                         rounded in fp32; r is written to r_f16 [M,K] as fp16 (the new
+ *                         residual stream) and t = float(r_f16[m,k]).
+ * The integer outputs of vq_residual_quantize are fully determined by this; those of the
+ * other two depend on the fp32 evaluation order of the reductions and on the device's
+ * exp / erf, within a few fp32 ulps of the exact t.
+ */
+int vq_gelu_quantize(const void* h_f16, int approximate, const float* chan_mul, int8_t* xq,
+                     float* x_scale, int M, int K, void* hip_stream);
+int vq_layernorm_quantize(const void* x_f16, const float* mod_scale, const float* mod_shift,
+                          int tokens_per_sample, float eps, const float* chan_mul, int8_t* xq,
+                          float* x_scale, int M, int K, void* hip_stream);
+int vq_residual_quantize(const void* x_f16, const void* y_f16, const float* gate, int tokens_per_sample,
+                         void* r_f16, const float* chan_mul, int8_t* xq, float* x_scale, int M, int K,
+                         void* hip_stream);
 
 /*
  * W8A8 integer GEMM with the dequantization epilogue (appendix "Hardware

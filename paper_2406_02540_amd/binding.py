@@ -23,6 +23,9 @@ STATUS_NAMES = {0: "VQ_OK", 1: "VQ_ERR_NULL", 2: "VQ_ERR_SHAPE", 3: "VQ_ERR_ALIG
 _P, _I, _SZ = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 SIGNATURES = {
     "vq_quantize_per_token": (_I, [_P, _P, _P, _P, _I, _I, _P]),
+    "vq_gelu_quantize": (_I, [_P, _I, _P, _P, _P, _I, _I, _P]),
+    "vq_layernorm_quantize": (_I, [_P, _P, _P, _I, ctypes.c_float, _P, _P, _P, _I, _I, _P]),
+    "vq_residual_quantize": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _I, _I, _P]),
     "vq_gemm_w8a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
     "vq_gemm_w4a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
     "vq_linear": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
@@ -104,6 +107,74 @@ def vq_quantize_per_token(x, chan_mul=None, xq=None, x_scale=None, stream=None):
     _check(lib().vq_quantize_per_token(_ptr(x), _ptr(chan_mul), _ptr(xq), _ptr(x_scale), M, K,
                                        _stream(stream)), "vq_quantize_per_token")
     return xq, x_scale
+
+
+def _quant_outputs(x, chan_mul, xq, x_scale):
+    M, K = x.shape
+    chan_mul = _dev(chan_mul, torch.float32, "chan_mul")
+    if chan_mul is not None and tuple(chan_mul.shape) != (K,):
+        raise ValueError("chan_mul must have shape [K]")
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if x_scale is None:
+        x_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
+    _dev(xq, torch.int8, "xq"), _dev(x_scale, torch.float32, "x_scale")
+    if tuple(xq.shape) != (M, K) or tuple(x_scale.shape) != (M,):
+        raise ValueError("output shapes")
+    return chan_mul, xq, x_scale
+
+
+def _per_sample(t, M, K, tokens_per_sample, name):
+    t = _dev(t, torch.float32, name)
+    if t is not None and tuple(t.shape) != ((M + tokens_per_sample - 1) // tokens_per_sample, K):
+        raise ValueError(f"{name} must have shape [ceil(M / tokens_per_sample), K]")
+    return t
+
+
+def vq_gelu_quantize(h, approximate=False, chan_mul=None, xq=None, x_scale=None, stream=None):
+    """GELU (exact or tanh form) fused with the quantizer: h fp16 [M,K] -> (xq, x_scale)."""
+    h = _dev(h, torch.float16, "h")
+    M, K = h.shape
+    chan_mul, xq, x_scale = _quant_outputs(h, chan_mul, xq, x_scale)
+    _check(lib().vq_gelu_quantize(_ptr(h), int(bool(approximate)), _ptr(chan_mul), _ptr(xq), _ptr(x_scale),
+                                  M, K, _stream(stream)), "vq_gelu_quantize")
+    return xq, x_scale
+
+
+def vq_layernorm_quantize(x, mod_scale=None, mod_shift=None, tokens_per_sample=None, eps=1e-6,
+                          chan_mul=None, xq=None, x_scale=None, stream=None):
+    """LayerNorm + (1 + scale) y + shift fused with the quantizer: x fp16 [M,K] -> (xq, x_scale)."""
+    x = _dev(x, torch.float16, "x")
+    M, K = x.shape
+    T = int(tokens_per_sample) if tokens_per_sample else max(M, 1)
+    mod_scale = _per_sample(mod_scale, M, K, T, "mod_scale")
+    mod_shift = _per_sample(mod_shift, M, K, T, "mod_shift")
+    chan_mul, xq, x_scale = _quant_outputs(x, chan_mul, xq, x_scale)
+    _check(lib().vq_layernorm_quantize(_ptr(x), _ptr(mod_scale), _ptr(mod_shift), T, float(eps),
+                                       _ptr(chan_mul), _ptr(xq), _ptr(x_scale), M, K, _stream(stream)),
+           "vq_layernorm_quantize")
+    return xq, x_scale
+
+
+def vq_residual_quantize(x, y, gate=None, tokens_per_sample=None, r=None, chan_mul=None, xq=None,
+                         x_scale=None, stream=None):
+    """r = x + gate * y fused with the quantizer: fp16 [M,K] twice -> (r fp16, xq, x_scale)."""
+    x = _dev(x, torch.float16, "x")
+    y = _dev(y, torch.float16, "y")
+    if y is None or tuple(y.shape) != tuple(x.shape):
+        raise ValueError("y must have the shape of x")
+    M, K = x.shape
+    T = int(tokens_per_sample) if tokens_per_sample else max(M, 1)
+    gate = _per_sample(gate, M, K, T, "gate")
+    if r is None:
+        r = torch.empty((M, K), dtype=torch.float16, device=x.device)
+    _dev(r, torch.float16, "r")
+    if tuple(r.shape) != (M, K):
+        raise ValueError("r must have the shape of x")
+    chan_mul, xq, x_scale = _quant_outputs(x, chan_mul, xq, x_scale)
+    _check(lib().vq_residual_quantize(_ptr(x), _ptr(y), _ptr(gate), T, _ptr(r), _ptr(chan_mul), _ptr(xq),
+                                      _ptr(x_scale), M, K, _stream(stream)), "vq_residual_quantize")
+    return r, xq, x_scale
 
 
 def _gemm(fn_name, xq, x_scale, w, w_cols_div, w_dtype, w_scale, bias, y, want_acc, stream):

@@ -87,6 +87,14 @@ int validate_quantize(const void* x, const void* chan_mul, const void* xq, const
     return VQ_OK;
 }
 
+// The fused variants keep the token in registers: whole 16-byte chunks, at most 16 per lane.
+int validate_fused(const void* x, const void* chan_mul, const void* xq, const void* x_scale, int M, int K) {
+    const int v = validate_quantize(x, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    if (K % 8 != 0 || K > VQ_MAX_FUSED_K) return VQ_ERR_SHAPE;
+    return VQ_OK;
+}
+
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
@@ -102,6 +110,48 @@ int vq_quantize_per_token(const void* x_f16, const float* chan_mul, int8_t* xq, 
     if (arch != VQ_OK) return arch;
     return launch_status(vq::launch_quantize_per_token(x_f16, chan_mul, xq, x_scale, M, K,
                                                        (hipStream_t)hip_stream));
+}
+
+int vq_gelu_quantize(const void* h_f16, int approximate, const float* chan_mul, int8_t* xq,
+                     float* x_scale, int M, int K, void* hip_stream) {
+    const int v = validate_fused(h_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    if (approximate != 0 && approximate != 1) return VQ_ERR_SHAPE;
+    if (M == 0) return VQ_OK;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_gelu_quantize(h_f16, approximate, chan_mul, xq, x_scale, M, K,
+                                                  (hipStream_t)hip_stream));
+}
+
+int vq_layernorm_quantize(const void* x_f16, const float* mod_scale, const float* mod_shift,
+                          int tokens_per_sample, float eps, const float* chan_mul, int8_t* xq,
+                          float* x_scale, int M, int K, void* hip_stream) {
+    const int v = validate_fused(x_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    if (tokens_per_sample <= 0 || !(eps >= 0.0f)) return VQ_ERR_SHAPE;
+    if (M == 0) return VQ_OK;
+    if ((mod_scale && misaligned(mod_scale)) || (mod_shift && misaligned(mod_shift))) return VQ_ERR_ALIGN;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_layernorm_quantize(x_f16, mod_scale, mod_shift, tokens_per_sample, eps,
+                                                       chan_mul, xq, x_scale, M, K,
+                                                       (hipStream_t)hip_stream));
+}
+
+int vq_residual_quantize(const void* x_f16, const void* y_f16, const float* gate, int tokens_per_sample,
+                         void* r_f16, const float* chan_mul, int8_t* xq, float* x_scale, int M, int K,
+                         void* hip_stream) {
+    const int v = validate_fused(x_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    if (tokens_per_sample <= 0) return VQ_ERR_SHAPE;
+    if (M == 0) return VQ_OK;
+    if (!y_f16 || !r_f16) return VQ_ERR_NULL;
+    if (misaligned(y_f16) || misaligned(r_f16) || (gate && misaligned(gate))) return VQ_ERR_ALIGN;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_residual_quantize(x_f16, y_f16, gate, tokens_per_sample, r_f16, chan_mul,
+                                                      xq, x_scale, M, K, (hipStream_t)hip_stream));
 }
 
 int vq_gemm_w8a8(const int8_t* xq, const float* x_scale, const int8_t* wq, const float* w_scale,

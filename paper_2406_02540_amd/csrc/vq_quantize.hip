@@ -12,17 +12,10 @@
 // its own, the two divisions per row are the correctly rounded IEEE ones, and
 // rounding to integer is v_rndne_f32 (halves to even).
 #include "vq_internal.h"
+#include "vq_quantize_row.h"
 
 namespace vq {
 namespace {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float float4v __attribute__((ext_vector_type(4)));
-typedef int int2v __attribute__((ext_vector_type(2)));
-
-constexpr int kWave = 64;
-constexpr int kQuantThreads = 256;
-constexpr int kRowsPerBlock = kQuantThreads / kWave;
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -30,83 +23,17 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
-// Rounds to the nearest integer (halves to even), clamps to [-qmax, qmax].
-__device__ __forceinline__ int quantize_one(float t, float inv, float qmax) {
-    float q = __builtin_rintf(t * inv);
-    q = fminf(fmaxf(q, -qmax), qmax);
-    return (int)q;
-}
-
-__device__ __forceinline__ int pack4(int a, int b, int c, int d) {
-    return (a & 0xFF) | ((b & 0xFF) << 8) | ((c & 0xFF) << 16) | (d << 24);
-}
-
-// LANES (64, 32 or 16) lanes of a wavefront share a token, so a wavefront holds
-// 64 / LANES tokens.  Lane s of a token owns its 16-byte chunks s, s + LANES, ...
-// (8 fp16 each): every load instruction of the wave covers contiguous pieces of
-// 16 * LANES bytes and every store half of that.  NCH = chunks per lane; LANES is
-// chosen so that K / 8 = NCH * LANES exactly where possible (K = 1152: 16 lanes x
-// 9 chunks), which keeps every lane busy on every instruction.  The row stays in
-// registers as fp32 between the absmax pass and the quantizing pass.
+// The token row held in registers (layout and steps: vq_quantize_row.h).  LANES is chosen
+// so that K / 8 = NCH * LANES exactly where possible (K = 1152: 16 lanes x 9 chunks),
+// which keeps every lane busy on every instruction.
 template <int NCH, int LANES, bool HAS_MUL>
 __global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave(
     const half8* __restrict__ x, const float4v* __restrict__ chan_mul, int2v* __restrict__ xq,
     float* __restrict__ x_scale, int M, int K8) {
-    constexpr int kRowsPerWave = kWave / LANES;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int sub = lane & (LANES - 1);
-    const long m = ((long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6)) * kRowsPerWave + lane / LANES;
-    const bool row_ok = m < M;  // lanes of a missing token idle but take part in the shuffles
-    const half8* row = x + (row_ok ? m : 0) * K8;
-
+    const RowLane<LANES> rl(M);
     float t[NCH][8];
-    float amax = 0.0f;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int c = i * LANES + sub;
-        if (row_ok && c < K8) {
-            const half8 v = __builtin_nontemporal_load(row + c);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[i][j] = (float)v[j];
-            if (HAS_MUL) {
-                const float4v m0 = chan_mul[2 * c], m1 = chan_mul[2 * c + 1];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    t[i][j] = t[i][j] * m0[j];
-                    t[i][4 + j] = t[i][4 + j] * m1[j];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(t[i][j]));
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[i][j] = 0.0f;
-        }
-    }
-#pragma unroll
-    for (int off = LANES / 2; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
-
-    float scale = 0.0f, inv = 0.0f;
-    if (amax != 0.0f) {
-        scale = amax / 127.0f;
-        inv = 127.0f / amax;
-    }
-    if (row_ok && sub == 0) x_scale[m] = scale;
-
-    int2v* qrow = xq + (row_ok ? m : 0) * K8;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int c = i * LANES + sub;
-        if (row_ok && c < K8) {
-            int q[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) q[j] = quantize_one(t[i][j], inv, 127.0f);
-            int2v o;
-            o.x = pack4(q[0], q[1], q[2], q[3]);
-            o.y = pack4(q[4], q[5], q[6], q[7]);
-            qrow[c] = o;
-        }
-    }
+    load_row<NCH, LANES, HAS_MUL>(x + (rl.row_ok ? rl.m : 0) * K8, rl.row_ok, rl.sub, K8, t, chan_mul);
+    fold_quantize_store<NCH, LANES, false>(t, nullptr, rl.row_ok, rl.sub, K8, rl.m, xq, x_scale);
 }
 
 __device__ __forceinline__ float block_max(float v, float* red) {

@@ -83,6 +83,30 @@ def test_quantize_argument_errors(lib):
     assert q(None, None, None, None, 0, 64, None) == 0  # empty: nothing to do
 
 
+def test_fused_quantizer_argument_errors(lib):
+    ge, ln, rs = lib.vq_gelu_quantize, lib.vq_layernorm_quantize, lib.vq_residual_quantize
+    F = ctypes.c_float
+    # the token must fit the registers: whole 16-byte chunks, K <= 8192
+    assert ge(P(A), 1, None, P(A), P(A), 4, 12, None) == 2
+    assert ge(P(A), 1, None, P(A), P(A), 4, 8200, None) == 2
+    assert ge(P(A), 2, None, P(A), P(A), 4, 64, None) == 2
+    assert ge(None, 1, None, P(A), P(A), 4, 64, None) == 1
+    assert ge(P(A + 8), 1, None, P(A), P(A), 4, 64, None) == 3
+    assert ge(None, 0, None, None, None, 0, 64, None) == 0
+    assert ln(P(A), None, None, 0, F(1e-6), None, P(A), P(A), 4, 64, None) == 2
+    assert ln(P(A), None, None, 2, F(-1.0), None, P(A), P(A), 4, 64, None) == 2
+    assert ln(P(A), P(A + 4), None, 2, F(1e-6), None, P(A), P(A), 4, 64, None) == 3
+    assert ln(P(A), None, None, 2, F(1e-6), None, P(A), None, 4, 64, None) == 1
+    assert rs(P(A), None, None, 2, P(A), None, P(A), P(A), 4, 64, None) == 1
+    assert rs(P(A), P(A), None, 2, None, None, P(A), P(A), 4, 64, None) == 1
+    assert rs(P(A), P(A), P(A + 4), 2, P(A), None, P(A), P(A), 4, 64, None) == 3
+    assert rs(P(A), P(A), None, 0, P(A), None, P(A), P(A), 4, 64, None) == 2
+    # valid arguments reach the device check: no gfx950 here
+    assert ge(P(A), 1, None, P(A), P(A), 4, 64, None) == 6
+    assert ln(P(A), None, None, 2, F(1e-6), None, P(A), P(A), 4, 64, None) == 6
+    assert rs(P(A), P(A), None, 2, P(A), None, P(A), P(A), 4, 64, None) == 6
+
+
 def test_gemm_argument_errors(lib):
     for g, kmult in ((lib.vq_gemm_w8a8, 16), (lib.vq_gemm_w4a8, 32)):
         ok = [P(A), P(A), P(A), P(A), None, P(A), None]
