@@ -174,6 +174,18 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                            k0 / 2);
     };
 
+    // One load of a wave's share of a stage (X and W loads alternate: s = 2 j + {0: X, 1: W}).
+    constexpr int kSingles = (W_BITS == 8) ? 8 : 6;  // packed 4-bit weights need only two W loads
+    auto issue_single = [&](const TileLoads& ld, int buf, int k0, int s) {
+        const int j = (W_BITS == 8 || s < 4) ? (s >> 1) : (s - 2);
+        const bool is_w = (W_BITS == 8 || s < 4) ? (s & 1) : false;
+        if (!is_w)
+            load_to_lds_16(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
+        else
+            load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
+                           W_BITS == 8 ? k0 : k0 / 2);
+    };
+
     // ---- LDS -> MFMA operand mapping -----------------------------------------
     // Operand rows of a 32x32x32 block: lane l supplies row l%32, 16 bytes of K
     // chosen by l/32; a stage holds four such K steps (chunks 2ks and 2ks+1).
@@ -254,80 +266,72 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
 
             const int8_t* xs = lds_x + buf * kXStage;
             const int8_t* ws = lds_w + buf * kWStage;
-            // Operand registers are double buffered: the LDS reads of K step ks+1 are
-            // issued before the MFMAs of step ks, which cover their latency.
-            auto read_step = [&](int ks, v4i(&xo)[4], v4i(&wo)[2]) __attribute__((always_inline)) {
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb) {
+            // Operand registers are double buffered: the LDS reads of K step ks+1 are issued
+            // among the MFMAs of step ks, which cover their latency.
+            // A K step = 8 MFMAs in four pieces of two.  A piece carries at most one global load
+            // (so that a wave never sits in the load queue while the matrix pipe waits for it:
+            // the 64 loads of a stage keep the CU's address path busy for half of the stage) and
+            // two LDS reads of the step after; sched_barrier(0) keeps the pieces apart.
+            //   reads of the next step in the order of their first use: w0 x0 | x1 x2 | x3 w1
+            auto read_one = [&](int ks, int r, v4i(&xo)[4], v4i(&wo)[2]) __attribute__((always_inline)) {
+                const bool past_k = K_TAIL && it == nk - 1 && it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K;
+                if (r == 0 || r == 5) {
+                    const int cb = (r == 0) ? 0 : 1;
                     if (W_BITS == 8)
                         wo[cb] = *(const v4i*)(ws + w_off(ks) + cb * 32 * kTileK);
                     else
                         wo[cb] = widen_nibbles(*(const v2i*)(ws + w_off(ks) + cb * 32 * (kTileK / 2)));
-                }
-#pragma unroll
-                for (int tb = 0; tb < 4; ++tb) xo[tb] = *(const v4i*)(xs + x_off(ks) + tb * 32 * kTileK);
-                if (K_TAIL && it == nk - 1) {
-                    // K is a multiple of 16 but not of 128: chunks past K hold bytes of the
-                    // next row (or nothing); a zero weight operand removes them.
-                    if (it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K) {
-#pragma unroll
-                        for (int cb = 0; cb < 2; ++cb) wo[cb] = v4i{0, 0, 0, 0};
-                    }
+                    // K is a multiple of 16 but not of 128: chunks past K hold bytes of the next
+                    // row (or nothing); a zero weight operand removes them.
+                    if (past_k) wo[cb] = v4i{0, 0, 0, 0};
+                } else {
+                    const int tb = r - 1;
+                    xo[tb] = *(const v4i*)(xs + x_off(ks) + tb * 32 * kTileK);
                 }
             };
-            auto mfma_step = [&](const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag) __attribute__((always_inline)) {
+            auto mfma_one = [&](int idx, const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag) __attribute__((always_inline)) {
+                const int cb = idx >> 2, tb = idx & 3;
+                if constexpr (decltype(zero_tag)::value)
+                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], kZero16, 0, 0, 0);
+                else
+                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], acc[cb][tb], 0, 0, 0);
+            };
+            // read_ks < 0: nothing left to read (the tile's last K step); first_load < 0: no loads
+            auto k_step = [&](const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag, int read_ks, v4i(&xo)[4],
+                              v4i(&wo)[2], int first_load) __attribute__((always_inline)) {
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                    for (int tb = 0; tb < 4; ++tb) {
-                        if constexpr (decltype(zero_tag)::value)
-                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], kZero16, 0, 0, 0);
-                        else
-                            acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], acc[cb][tb], 0, 0, 0);
+                for (int p = 0; p < 4; ++p) {
+                    if (fetch && first_load >= 0 && first_load + p < kSingles)
+                        issue_single(ld, buf ^ 1, fk0, first_load + p);
+                    mfma_one(2 * p, xi, wi, zero_tag);
+                    mfma_one(2 * p + 1, xi, wi, zero_tag);
+                    if (read_ks >= 0 && p < 3) {
+                        read_one(read_ks, 2 * p, xo, wo);
+                        read_one(read_ks, 2 * p + 1, xo, wo);
+                        if (W_BITS == 8) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
                     }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             };
             constexpr std::false_type kAccumulate{};
-            // Inside a K step the six LDS reads of the next step are dealt out one behind each of
-            // the first six MFMAs (sched_group_barrier), so that a wave never leaves the matrix
-            // pipe without work while it issues a run of reads; sched_barrier(0) fences keep
-            // the steps apart (the scheduler would otherwise sink reads next to their uses).
-            auto interleave = [&]() __attribute__((always_inline)) {
+            if (FIRST) {
+                // nothing deferred to cover them: the first K step's operands are read up front
 #pragma unroll
-                for (int i = 0; i < 6; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            };
-            if (fetch) {  // this wave's share of the next stage's loads, first half
-                issue_part(ld, buf ^ 1, fk0, 0);
-                issue_part(ld, buf ^ 1, fk0, 1);
+                for (int r = 0; r < 6; ++r) read_one(0, r, xf[0], wf[0]);
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                k_step(xf[1], wf[1], kAccumulate, 0, xf[0], wf[0], 0);  // K step 3 of the previous stage
             }
-            __builtin_amdgcn_sched_barrier(0);
-            read_step(0, xf[0], wf[0]);
-            if (!FIRST) {
-                mfma_step(xf[1], wf[1], kAccumulate);  // K step 3 of the previous stage
-                if (W_BITS == 8) interleave();
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (fetch) {  // second half
-                issue_part(ld, buf ^ 1, fk0, 2);
-                issue_part(ld, buf ^ 1, fk0, 3);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            read_step(1, xf[1], wf[1]);
-            mfma_step(xf[0], wf[0], first_tag);  // K step 0
-            if (W_BITS == 8) interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            read_step(2, xf[0], wf[0]);
-            mfma_step(xf[1], wf[1], kAccumulate);  // K step 1
-            if (W_BITS == 8) interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            read_step(3, xf[1], wf[1]);
-            mfma_step(xf[0], wf[0], kAccumulate);  // K step 2
-            if (W_BITS == 8) interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            if (LAST) mfma_step(xf[1], wf[1], kAccumulate);  // K step 3 (otherwise at the start of the next stage)
+            k_step(xf[0], wf[0], first_tag, 1, xf[1], wf[1], FIRST ? 0 : 4);  // K step 0
+            k_step(xf[1], wf[1], kAccumulate, 2, xf[0], wf[0], FIRST ? 4 : -1);  // K step 1
+            k_step(xf[0], wf[0], kAccumulate, 3, xf[1], wf[1], -1);  // K step 2
+            // K step 3 (otherwise at the start of the next stage)
+            if (LAST) k_step(xf[1], wf[1], kAccumulate, -1, xf[0], wf[0], -1);
             if (!more) park_scales();
             // The stage requested above has landed for every wave and every wave is done
             // reading this one.  After the last stage this also says: the scales are in LDS,
