@@ -52,13 +52,15 @@ def _load():
         lib.oracle_gelu.argtypes = [p, ci, p, i64, i64]
         lib.oracle_layernorm_modulate.argtypes = [p, p, p, i64, ctypes.c_double, p, i64, i64]
         lib.oracle_residual.argtypes = [p, p, p, i64, p, i64, i64]
+        lib.oracle_gemm_f16.argtypes = [p, p, p, p, i64, i64, i64]
+        lib.oracle_quantize_static.argtypes = [p, p, ctypes.c_float, p, i64, i64]
         lib.oracle_quantize_weight.argtypes = [p, p, ci, p, p, i64, i64]
         lib.oracle_pack_int4.argtypes = [p, p, i64, i64]
         lib.oracle_unpack_int4.argtypes = [p, p, i64, i64]
         lib.oracle_gemm_i8.argtypes = [p, p, p, i64, i64, i64]
         lib.oracle_dequant.argtypes = [p, p, p, p, p, i64, i64]
         lib.oracle_linear.argtypes = [p, p, p, ci, p, p, p, p, p, p, p, i64, i64, i64]
-        for name in ("oracle_quantize_rows_f32", "oracle_gelu", "oracle_layernorm_modulate",
+        for name in ("oracle_gemm_f16", "oracle_quantize_static", "oracle_quantize_rows_f32", "oracle_gelu", "oracle_layernorm_modulate",
                      "oracle_residual",
                      "oracle_quantize_per_token", "oracle_quantize_weight", "oracle_pack_int4",
                      "oracle_unpack_int4", "oracle_gemm_i8", "oracle_dequant", "oracle_linear"):
@@ -193,6 +195,30 @@ def residual_quantize(x_f16, y_f16, gate=None, tokens_per_sample=None, chan_mul=
     """Residual add fused with the quantizer: returns (r fp16, xq, x_scale)."""
     r = residual(x_f16, y_f16, gate, tokens_per_sample)
     return (r,) + quantize_per_token(r, chan_mul)
+
+
+def gemm_f16(x_f16, w_f16, bias_f16=None):
+    """FP16 linear layer: X fp16 [M,K], W fp16 [N,K] -> fp16 [M,N], summed in fp64."""
+    xb, wb = _f16(x_f16), _f16(w_f16)
+    M, K = xb.shape
+    N = wb.shape[0]
+    if wb.shape != (N, K):
+        raise ValueError("weight shape")
+    b = None if bias_f16 is None else _f16(bias_f16)
+    y = np.empty((M, N), np.uint16)
+    _check(_load().oracle_gemm_f16(_ptr(xb), _ptr(wb), _ptr(b), _ptr(y), M, N, K), "gemm_f16")
+    return y.view(np.float16)
+
+
+def quantize_static(x_f16, scale: float, chan_mul=None):
+    """One fixed scale for the whole tensor: X fp16 [M,K] -> xq int8 [M,K], clipped at +-127."""
+    xb = _f16(x_f16)
+    M, K = xb.shape
+    cm = None if chan_mul is None else _arr(chan_mul, np.float32, (K,))
+    xq = np.empty((M, K), np.int8)
+    _check(_load().oracle_quantize_static(_ptr(xb), _ptr(cm), ctypes.c_float(float(np.float32(scale))),
+                                          _ptr(xq), M, K), "quantize_static")
+    return xq
 
 
 def quantize_weight(w_f32, chan_s=None, bits: int = 8):

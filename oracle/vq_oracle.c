@@ -358,6 +358,52 @@ int oracle_dequant(const int32_t* acc, const float* x_scale, const float* w_scal
     return ORACLE_OK;
 }
 
+/* ---- comparison points of Sec. 5.3 "Hardware Resource Savings" -----------------
+ * The paper measures its INT8 layers against FP16 layers (about 2x) and against a
+ * "naive" W8A8 baseline without dynamic, fine-grained parameters.  Both are
+ * stated here so that the GPU counterparts can be checked.                      */
+
+/* FP16 linear layer: y[m,n] = fp16( sum_k x[m,k] w[n,k] + bias[n] ), the sum in fp64
+ * (the products of two fp16 values are exact in fp64).                           */
+int oracle_gemm_f16(const uint16_t* x_f16, const uint16_t* w_f16, const uint16_t* bias_f16,
+                    uint16_t* y_f16, int64_t M, int64_t N, int64_t K) {
+    if (!x_f16 || !w_f16 || !y_f16 || M < 0 || N < 0 || K <= 0) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double sum = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                sum += (double)oracle_half_to_float(x_f16[m * K + k]) *
+                       (double)oracle_half_to_float(w_f16[n * K + k]);
+            if (bias_f16) sum += (double)oracle_half_to_float(bias_f16[n]);
+            y_f16[m * N + n] = oracle_float_to_half((float)sum);
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* Static activation quantizer: one scale for the whole tensor, fixed beforehand
+ * (Sec. 4.1 describes it as what dynamic token-wise parameters replace).
+ * inv = 1 / scale once in fp32; q = clamp(rint(t * inv), -127, 127) with
+ * t = float(x) * chan_mul[k]: values beyond 127 * scale are clipped.              */
+int oracle_quantize_static(const uint16_t* x_f16, const float* chan_mul, float scale,
+                           int8_t* xq, int64_t M, int64_t K) {
+    if (!x_f16 || !xq || M < 0 || K <= 0 || !(scale > 0.0f)) return ORACLE_ERR_ARG;
+    const float inv = 1.0f / scale;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t k = 0; k < K; ++k) {
+            float t = oracle_half_to_float(x_f16[m * K + k]);
+            if (chan_mul) t = t * chan_mul[k];
+            float q = rintf(t * inv);
+            if (q > 127.0f) q = 127.0f;
+            if (q < -127.0f) q = -127.0f;
+            xq[m * K + k] = (int8_t)q;
+        }
+    }
+    return ORACLE_OK;
+}
+
 /* ---- the whole layer, steps in the order above ---------------------------
  * w is int8 [N,K] when w_bits == 8, packed nibbles [N,K/2] when w_bits == 4.
  * xq_out [M,K], x_scale_out [M] and acc_out [M,N] are caller scratch and are

@@ -194,3 +194,62 @@ def test_fused_front_ends_compose_the_pinned_parts(oracle):
     assert np.array_equal(r.view(np.uint16), oracle.residual(x, y, sc, T).view(np.uint16))
     q2, s2 = oracle.quantize_per_token(r, cm)
     assert np.array_equal(q, q2) and np.array_equal(s, s2)
+
+
+# ---- comparison points: FP16 linear layer, static quantizer (Sec. 5.3) ----------------
+
+def test_gemm_f16_against_numpy_float64(oracle):
+    g = np.random.default_rng(21)
+    for M, N, K in ((3, 5, 7), (17, 9, 300), (4, 33, 1152)):
+        x = g.standard_normal((M, K)).astype(np.float16)
+        w = (g.standard_normal((N, K)) * 0.05).astype(np.float16)
+        b = (g.standard_normal(N) * 0.1).astype(np.float16)
+        want = (x.astype(np.float64) @ w.astype(np.float64).T + b.astype(np.float64)).astype(np.float32).astype(np.float16)
+        got = oracle.gemm_f16(x, w, b)
+        assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+        want = (x.astype(np.float64) @ w.astype(np.float64).T).astype(np.float32).astype(np.float16)
+        assert np.array_equal(oracle.gemm_f16(x, w).view(np.uint16), want.view(np.uint16))
+
+
+def test_gemm_f16_exact_cases(oracle):
+    # small integers: every product and sum is exact, so the result is the integer matmul
+    g = np.random.default_rng(22)
+    x = g.integers(-8, 9, (6, 40)).astype(np.float16)
+    w = g.integers(-4, 5, (10, 40)).astype(np.float16)
+    want = x.astype(np.int64) @ w.astype(np.int64).T
+    assert np.array_equal(oracle.gemm_f16(x, w).astype(np.int64), want)
+    # identity weights select the activations; a transposed operand would not
+    x = g.standard_normal((5, 8)).astype(np.float16)
+    assert np.array_equal(oracle.gemm_f16(x, np.eye(8, dtype=np.float16)).view(np.uint16), x.view(np.uint16))
+    w = np.zeros((3, 8), np.float16)
+    w[0, 1] = 1; w[1, 5] = 2; w[2, 7] = -1
+    got = oracle.gemm_f16(x, w)
+    assert np.array_equal(got[:, 0], x[:, 1]) and np.array_equal(got[:, 1], (2 * x[:, 5].astype(np.float32)).astype(np.float16))
+    assert np.array_equal(got[:, 2], -x[:, 7])
+
+
+def test_quantize_static_hand_examples_and_clipping(oracle):
+    # scale 0.5 (inv = 2 exactly): 0.25 -> 0.5 -> 0 (tie to even), 0.75 -> 1.5 -> 2, 1.25 -> 2.5 -> 2
+    x = np.array([[0.25, 0.75, 1.25, -0.25, -0.75, 63.5, 63.75, 100.0, -100.0, 0.0]], np.float16)
+    assert oracle.quantize_static(x, 0.5)[0].tolist() == [0, 2, 2, 0, -2, 127, 127, 127, -127, 0]
+    # the balancing factor comes first
+    cm = np.full(10, 0.5, np.float32)
+    assert oracle.quantize_static(x, 0.5, cm)[0].tolist() == [0, 1, 1, 0, -1, 64, 64, 100, -100, 0]
+    with pytest.raises(oracle.OracleError):
+        oracle.quantize_static(x, 0.0)
+
+
+def test_quantize_static_against_numpy_and_error_bound(oracle):
+    g = np.random.default_rng(23)
+    x = (g.standard_normal((9, 257)) * 3).astype(np.float16)
+    cm = np.exp(g.uniform(-1, 1, 257)).astype(np.float32)
+    scale = np.float32(0.037)
+    inv = np.float32(1.0) / scale
+    want = np.clip(np.rint((x.astype(np.float32) * cm) * inv), -127, 127).astype(np.int8)
+    got = oracle.quantize_static(x, float(scale), cm)
+    assert np.array_equal(got, want)
+    t = x.astype(np.float64) * cm.astype(np.float64)
+    inside = np.abs(t) <= 127 * float(scale)
+    err = np.abs(got.astype(np.float64) * float(scale) - t)
+    assert np.all(err[inside] <= 0.5 * float(scale) * (1 + 2.0 ** -15))
+    assert np.all(np.abs(got[~inside]) == 127)
