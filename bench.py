@@ -42,7 +42,7 @@ def parse():
     p.add_argument("--no-ceilings", action="store_true",
                    help="skip the measured ceilings (register-only MFMA loop on realistic operands, copy kernel)")
     p.add_argument("--no-fused", action="store_true",
-                   help="skip the timings of the quantizer fused behind LayerNorm / GELU / residual add")
+                   help="skip the timings of the fused quantizers and of the FP16 / static comparison kernels")
     p.add_argument("--copy-calibration", action="store_true",
                    help="only run a plain 1 GiB device copy a few times (reference for the "
                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -225,6 +225,46 @@ def main():
                                   GBps=round(nbytes / dt / 1e9, 1), frac_of_hbm_peak=round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4)))
                 log(f"fused {name:20s} -> {s.name:4s} {s.M}x{s.K}: {dt * 1e6:7.1f} us  {nbytes / dt / 1e9:6.0f} GB/s")
 
+    # ---- the paper's comparison points on the same device (Sec. 5.3): FP16 layers, static W8A8 ---------
+    comparison = None
+    if not args.no_fused:
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nrep)]
+            for a, b in evs:
+                a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+        rows = []
+        for L, pl in zip(layers, per_layer):
+            s = L["spec"]
+            if s.M < 1024:
+                continue
+            w16 = torch.from_numpy(L["data"].w.astype(np.float16)).cuda()
+            t16 = timed(lambda: vq.vq_gemm_f16(L["x"], w16, L["bias"], y=L["y"]))
+            ts = timed(lambda: vq.vq_quantize_static(L["x"], 0.05, L["cm"], xq=L["xq"]))
+            tq, tg = pl["quant_us"] * 1e-6, pl["gemm_us"] * 1e-6
+            rows.append(dict(layer=s.name, fp16_gemm_us=round(t16 * 1e6, 2), fp16_TFLOPS=round(s.ops / t16 / 1e12, 1),
+                             static_quant_us=round(ts * 1e6, 2),
+                             int8_gemm_vs_fp16=round(t16 / tg, 3),
+                             int8_layer_vs_fp16=round(t16 / (tq + tg), 3),
+                             static_layer_vs_fp16=round(t16 / (ts + tg), 3)))
+            log(f"compare {s.name:4s}: fp16 GEMM {t16 * 1e6:7.1f} us ({s.ops / t16 / 1e12:5.0f} TFLOP/s)  int8 GEMM x{t16 / tg:4.2f}  "
+                f"int8 layer (dynamic quant) x{t16 / (tq + tg):4.2f}  (static quant, {ts * 1e6:5.1f} us) x{t16 / (ts + tg):4.2f}")
+            del w16
+        t16s = sum(r["fp16_gemm_us"] for r in rows)
+        tg_s = sum(p["gemm_us"] for L, p in zip(layers, per_layer) if L["spec"].M >= 1024)
+        tq_s = sum(p["quant_us"] for L, p in zip(layers, per_layer) if L["spec"].M >= 1024)
+        ts_s = sum(r["static_quant_us"] for r in rows)
+        comparison = dict(what="fp16 layer = vq_gemm_f16 (same tiling, fp16 MFMA); speedups are fp16 time / int8 time over "
+                               "the layers with M >= 1024",
+                          int8_gemm_vs_fp16=round(t16s / tg_s, 3),
+                          int8_layer_dynamic_vs_fp16=round(t16s / (tg_s + tq_s), 3),
+                          int8_layer_static_vs_fp16=round(t16s / (tg_s + ts_s), 3),
+                          paper="about 2x for the INT8 kernels, 1.73x -> 1.71x end to end for static -> dynamic (A100, Sec. 5.3)",
+                          per_layer=rows)
+
     # ---- the CPU oracle timed beside it, on a bounded sample of the same workload ---------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -291,6 +331,7 @@ def main():
         "roofline_quantizer": roofline_q,
         "cpu_baseline": cpu,
         "fused_quantizers": fused,
+        "comparison": comparison,
         "measured_ceilings": ceilings,
         "per_layer": [{k: (round(v, 2) if isinstance(v, float) else v) for k, v in p.items()} for p in per_layer],
     }

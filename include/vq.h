@@ -110,6 +110,25 @@ int vq_residual_quantize(const void* x_f16, const void* y_f16, const float* gate
                          void* hip_stream);
 
 /*
+ * The two comparison points of the paper's hardware evaluation (Sec. 5.3 "Hardware
+ * Resource Savings": the INT8 layers against FP16 layers, and against a "naive" W8A8
+ * baseline without dynamic token-wise parameters), on the same device and with the same
+ * tiling as vq_gemm_w8a8.  They are measured next to the quantized layer, not part of it.
+ *
+ * vq_gemm_f16:        y[m,n] = fp16(sum_k x[m,k] * w[n,k] + bias[n]), fp16 operands,
+ *                     products exact, sums in fp32 (matrix-core order).  x_f16 [M,K],
+ *                     w_f16 [N,K], bias_f16 [N] or NULL, y_f16 [M,N]; K % 8 == 0.
+ * vq_quantize_static: xq[m,k] = clamp(rne(float(x[m,k]) * chan_mul[k] * (1 / scale)),
+ *                     -127, 127) with one `scale` (host value, > 0) for the whole tensor
+ *                     and one fp32 reciprocal; values beyond 127 * scale are clipped.
+ *                     The caller passes the same scale for every token to vq_gemm_w8a8.
+ */
+int vq_gemm_f16(const void* x_f16, const void* w_f16, const void* bias_f16, void* y_f16, int M, int N, int K,
+                void* hip_stream);
+int vq_quantize_static(const void* x_f16, const float* chan_mul, float scale, int8_t* xq, int M, int K,
+                       void* hip_stream);
+
+/*
  * W8A8 integer GEMM with the dequantization epilogue (appendix "Hardware
  * implementation of quantized linear layers": the integer products are summed
  * along the input channels, the token-wise and output-channel-wise scales

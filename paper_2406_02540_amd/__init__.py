@@ -6,12 +6,14 @@
 from .binding import (  # noqa: F401
     VqError,
     vq_gelu_quantize,
+    vq_gemm_f16,
     vq_gemm_w4a8,
     vq_gemm_w8a8,
     vq_layernorm_quantize,
     vq_linear,
     vq_linear_workspace_bytes,
     vq_quantize_per_token,
+    vq_quantize_static,
     vq_quantize_weight,
     vq_residual_quantize,
 )

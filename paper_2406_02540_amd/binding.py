@@ -26,6 +26,8 @@ SIGNATURES = {
     "vq_gelu_quantize": (_I, [_P, _I, _P, _P, _P, _I, _I, _P]),
     "vq_layernorm_quantize": (_I, [_P, _P, _P, _I, ctypes.c_float, _P, _P, _P, _I, _I, _P]),
     "vq_residual_quantize": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _I, _I, _P]),
+    "vq_gemm_f16": (_I, [_P, _P, _P, _P, _I, _I, _I, _P]),
+    "vq_quantize_static": (_I, [_P, _P, ctypes.c_float, _P, _I, _I, _P]),
     "vq_gemm_w8a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
     "vq_gemm_w4a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
     "vq_linear": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
@@ -175,6 +177,43 @@ def vq_residual_quantize(x, y, gate=None, tokens_per_sample=None, r=None, chan_m
     _check(lib().vq_residual_quantize(_ptr(x), _ptr(y), _ptr(gate), T, _ptr(r), _ptr(chan_mul), _ptr(xq),
                                       _ptr(x_scale), M, K, _stream(stream)), "vq_residual_quantize")
     return r, xq, x_scale
+
+
+def vq_gemm_f16(x, w, bias=None, y=None, stream=None):
+    """FP16 comparison layer: x fp16 [M,K], w fp16 [N,K] (+ bias fp16 [N]) -> y fp16 [M,N]."""
+    x = _dev(x, torch.float16, "x")
+    w = _dev(w, torch.float16, "w")
+    M, K = x.shape
+    N = w.shape[0]
+    if tuple(w.shape) != (N, K):
+        raise ValueError("weight shape does not match K")
+    bias = _dev(bias, torch.float16, "bias")
+    if bias is not None and tuple(bias.shape) != (N,):
+        raise ValueError("bias must have shape [N]")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _dev(y, torch.float16, "y")
+    if tuple(y.shape) != (M, N):
+        raise ValueError("y must have shape [M,N]")
+    _check(lib().vq_gemm_f16(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), M, N, K, _stream(stream)), "vq_gemm_f16")
+    return y
+
+
+def vq_quantize_static(x, scale, chan_mul=None, xq=None, stream=None):
+    """One fixed scale for the whole tensor: x fp16 [M,K] -> xq int8 [M,K] (clipped at +-127)."""
+    x = _dev(x, torch.float16, "x")
+    M, K = x.shape
+    chan_mul = _dev(chan_mul, torch.float32, "chan_mul")
+    if chan_mul is not None and tuple(chan_mul.shape) != (K,):
+        raise ValueError("chan_mul must have shape [K]")
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    _dev(xq, torch.int8, "xq")
+    if tuple(xq.shape) != (M, K):
+        raise ValueError("xq must have shape [M,K]")
+    _check(lib().vq_quantize_static(_ptr(x), _ptr(chan_mul), float(scale), _ptr(xq), M, K, _stream(stream)),
+           "vq_quantize_static")
+    return xq
 
 
 def _gemm(fn_name, xq, x_scale, w, w_cols_div, w_dtype, w_scale, bias, y, want_acc, stream):

@@ -154,6 +154,32 @@ int vq_residual_quantize(const void* x_f16, const void* y_f16, const float* gate
                                                       xq, x_scale, M, K, (hipStream_t)hip_stream));
 }
 
+int vq_gemm_f16(const void* x_f16, const void* w_f16, const void* bias_f16, void* y_f16, int M, int N, int K,
+                void* hip_stream) {
+    if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K || K % 8 != 0) return VQ_ERR_SHAPE;
+    if (M == 0 || N == 0) return VQ_OK;
+    if (!x_f16 || !w_f16 || !y_f16) return VQ_ERR_NULL;
+    if (misaligned(x_f16) || misaligned(w_f16) || misaligned(y_f16) || (bias_f16 && misaligned(bias_f16)))
+        return VQ_ERR_ALIGN;
+    int num_cus = 0;
+    const int arch = check_arch(&num_cus);
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_gemm((const int8_t*)x_f16, nullptr, w_f16, 16, nullptr, bias_f16, y_f16,
+                                         nullptr, M, N, K, num_cus, (hipStream_t)hip_stream));
+}
+
+int vq_quantize_static(const void* x_f16, const float* chan_mul, float scale, int8_t* xq, int M, int K,
+                       void* hip_stream) {
+    if (M < 0 || K <= 0 || K > VQ_MAX_K || !(scale > 0.0f)) return VQ_ERR_SHAPE;
+    if (M == 0) return VQ_OK;
+    if (!x_f16 || !xq) return VQ_ERR_NULL;
+    if (misaligned(x_f16) || misaligned(xq) || (chan_mul && misaligned(chan_mul))) return VQ_ERR_ALIGN;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_quantize_static(x_f16, chan_mul, 1.0f / scale, xq, M, K,
+                                                    (hipStream_t)hip_stream));
+}
+
 int vq_gemm_w8a8(const int8_t* xq, const float* x_scale, const int8_t* wq, const float* w_scale,
                  const void* bias_f16, void* y_f16, int32_t* acc_out, int M, int N, int K,
                  void* hip_stream) {

@@ -95,6 +95,22 @@ struct TileLoads {
     int voff_x[4], voff_w[4];
 };
 
+// One 32 x 32 block: int8 operands (32 values of K per lane pair) into int32 sums, or,
+// for the fp16 comparison layer, fp16 operands (16 values of K) into fp32 sums.  Both take
+// 16 bytes of each operand per lane and as long to issue.
+typedef float v16f __attribute__((ext_vector_type(16)));
+template <int W_BITS>
+struct AccOf { typedef v16i type; };
+template <>
+struct AccOf<16> { typedef v16f type; };
+__device__ __forceinline__ v16i mfma_block(v4i w, v4i x, v16i c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
+}
+__device__ __forceinline__ v16f mfma_block(v4i w, v4i x, v16f c) {
+    // (a cast between vector types of one size reinterprets the bits)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16((half8)w, (half8)x, c, 0, 0, 0);
+}
+
 // K_TAIL:  K is a multiple of 16 but not of 128 (the last stage is partly past K).
 // GENERIC: any N and an optional copy of the integer sums; stores go out element by
 //          element.  The fast variant needs N % 8 == 0 and writes whole lines.
@@ -117,8 +133,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     // leaves one working wave on every SIMD.
     const int wave_t = wave & 1;   // which 128 tokens
     const int wave_c = wave >> 1;  // which 64 channels
-    const int K = a.K;
-    constexpr int kWDiv = (W_BITS == 8) ? 1 : 2;  // values of K per stored byte
+    // (W_BITS == 16: fp16 operands, the comparison layer; rows are 2 K bytes and everything up
+    // to the MFMA itself treats them like int8 rows of that many bytes)
+    const int K = (W_BITS == 16) ? 2 * a.K : a.K;      // bytes per activation row
+    constexpr int kWDiv = (W_BITS == 4) ? 2 : 1;        // activation bytes per weight byte
     const int nk = (K + kTileK - 1) / kTileK;
 
     // ---- global -> LDS mapping ---------------------------------------------
@@ -151,7 +169,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         for (int j = 0; j < 4; ++j) {
             const int r = (wave + 8 * j) * 8 + (l >> 3);
             ld.voff_x[j] = min(r, t.rows_x - 1) * K + ld_chunk16;
-            if (W_BITS == 8) {
+            if (W_BITS != 4) {
                 ld.voff_w[j] = min(w_row_to_channel(r), t.rows_w - 1) * K + ld_chunk16;
             } else {
                 const int r4 = (wave + 8 * (j & 1)) * 16 + (l >> 2);
@@ -167,7 +185,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     // the stage being multiplied, so that no wave sits in a queue of eight loads.
     auto issue_part = [&](const TileLoads& ld, int buf, int k0, int j) {
         load_to_lds_16(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
-        if (W_BITS == 8)
+        if (W_BITS != 4)
             load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j], k0);
         else if (j < 2)
             load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
@@ -175,15 +193,15 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     };
 
     // One load of a wave's share of a stage (X and W loads alternate: s = 2 j + {0: X, 1: W}).
-    constexpr int kSingles = (W_BITS == 8) ? 8 : 6;  // packed 4-bit weights need only two W loads
+    constexpr int kSingles = (W_BITS != 4) ? 8 : 6;  // packed 4-bit weights need only two W loads
     auto issue_single = [&](const TileLoads& ld, int buf, int k0, int s) {
-        const int j = (W_BITS == 8 || s < 4) ? (s >> 1) : (s - 2);
-        const bool is_w = (W_BITS == 8 || s < 4) ? (s & 1) : false;
+        const int j = (W_BITS != 4 || s < 4) ? (s >> 1) : (s - 2);
+        const bool is_w = (W_BITS != 4 || s < 4) ? (s & 1) : false;
         if (!is_w)
             load_to_lds_16(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
         else
             load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
-                           W_BITS == 8 ? k0 : k0 / 2);
+                           W_BITS != 4 ? k0 : k0 / 2);
     };
 
     // ---- LDS -> MFMA operand mapping -----------------------------------------
@@ -193,12 +211,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     // byte offset of step ks is that of step 0 with 32 ks XOR-ed in.
     const int fr_row = lane & 31;
     const int x_off0 = (wave_t * 128 + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4);
-    const int w_off0 = (W_BITS == 8)
+    const int w_off0 = (W_BITS != 4)
                            ? (wave_c * 64 + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4)
                            // 8 bytes of nibbles: 16-byte chunk ks (swizzled by (row/4)%4), half l/32
                            : (wave_c * 64 + fr_row) * (kTileK / 2) + (((fr_row >> 2) & 3) << 4) + (lane >> 5) * 8;
     auto x_off = [&](int ks) { return x_off0 ^ (ks << 5); };
-    auto w_off = [&](int ks) { return w_off0 ^ (ks << (W_BITS == 8 ? 5 : 4)); };
+    auto w_off = [&](int ks) { return w_off0 ^ (ks << (W_BITS != 4 ? 5 : 4)); };
 
     // ---- the tiles of this workgroup -------------------------------------------
     int idx = blockIdx.x / kXcds;
@@ -229,10 +247,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         if (wave < 4) {
             const int i = wave * 64 + opaque(lane);
             if (cur.ch0 + i < a.N) {
-                pre_ws = a.w_scale[cur.ch0 + i];
+                if (W_BITS != 16) pre_ws = a.w_scale[cur.ch0 + i];
                 if (a.bias) pre_b = a.bias[cur.ch0 + i];
             }
-            if (cur.tok0 + i < a.M) pre_xs = a.x_scale[cur.tok0 + i];
+            if (W_BITS != 16 && cur.tok0 + i < a.M) pre_xs = a.x_scale[cur.tok0 + i];
         }
 
         auto park_scales = [&]() {
@@ -244,9 +262,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             }
         };
 
-        v16i acc[2][4];
+        typedef typename AccOf<W_BITS>::type acc_t;
+        acc_t acc[2][4];
         v4i xf[2][4], wf[2][2];  // operand registers, double buffered; [1] carries K step 3 across stages
-        const v16i kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        const acc_t kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
         // One stage = four K steps of 8 MFMAs per wave.  The schedule is skewed by one K step:
         // the MFMAs of a stage's last K step are issued at the start of the next stage, behind
@@ -277,7 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                 const bool past_k = K_TAIL && it == nk - 1 && it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K;
                 if (r == 0 || r == 5) {
                     const int cb = (r == 0) ? 0 : 1;
-                    if (W_BITS == 8)
+                    if (W_BITS != 4)
                         wo[cb] = *(const v4i*)(ws + w_off(ks) + cb * 32 * kTileK);
                     else
                         wo[cb] = widen_nibbles(*(const v2i*)(ws + w_off(ks) + cb * 32 * (kTileK / 2)));
@@ -292,9 +311,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
             auto mfma_one = [&](int idx, const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag) __attribute__((always_inline)) {
                 const int cb = idx >> 2, tb = idx & 3;
                 if constexpr (decltype(zero_tag)::value)
-                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], kZero16, 0, 0, 0);
+                    acc[cb][tb] = mfma_block(wi[cb], xi[tb], kZero16);
                 else
-                    acc[cb][tb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wi[cb], xi[tb], acc[cb][tb], 0, 0, 0);
+                    acc[cb][tb] = mfma_block(wi[cb], xi[tb], acc[cb][tb]);
             };
             // read_ks < 0: nothing left to read (the tile's last K step); first_load < 0: no loads
             auto k_step = [&](const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag, int read_ks, v4i(&xo)[4],
@@ -308,7 +327,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                     if (read_ks >= 0 && p < 3) {
                         read_one(read_ks, 2 * p, xo, wo);
                         read_one(read_ks, 2 * p + 1, xo, wo);
-                        if (W_BITS == 8) {
+                        if (W_BITS != 4) {
                             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
                             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
                             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -417,8 +436,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                     half8 out;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const float f = (float)acc[b][tb][r0 + e] * xsc;
-                        float y = __builtin_fmaf(f, wsc[8 * g + e], bsc[8 * g + e]);
+                        float y;
+                        if (W_BITS == 16) {  // the fp32 sum of the fp16 products, plus the bias
+                            y = (float)acc[b][tb][r0 + e] + bsc[8 * g + e];
+                        } else {
+                            const float f = (float)acc[b][tb][r0 + e] * xsc;
+                            y = __builtin_fmaf(f, wsc[8 * g + e], bsc[8 * g + e]);
+                        }
                         // keep the fp32 result as such: the narrowing below then is a plain
                         // round-to-nearest-even of it in every variant of this kernel (a fused
                         // multiply-add-narrow instruction would round only once)
@@ -435,7 +459,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
                             if (c0 + e < a.N) {
                                 a.y[tok * a.N + c0 + e] = out[e];
                                 if (a.acc_out) {
-                                    const int v = acc[b][tb][r0 + e];
+                                    const int v = (int)acc[b][tb][r0 + e];
                                     a.acc_out[tok * a.N + c0 + e] = (W_BITS == 4) ? (v >> 4) : v;
                                 }
                             }
@@ -491,7 +515,7 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     if (tiles > 0x7FFFFFF0l) return hipErrorInvalidValue;
     // A problem whose large tiles would leave more than half of the CUs idle is latency
     // bound: the small-tile kernel puts many more loads in flight.
-    if (tiles * 2 <= num_cus)
+    if (tiles * 2 <= num_cus && w_bits != 16)
         return launch_gemm_small(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, acc_out, M, N, K, stream);
     a.tiles = (int)tiles;
     a.tiles_per_xcd = (a.tiles + kXcds - 1) / kXcds;
@@ -499,13 +523,16 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     const int cus_per_xcd = num_cus >= kXcds ? num_cus / kXcds : 1;
     a.slots = a.tiles_per_xcd < cus_per_xcd ? a.tiles_per_xcd : cus_per_xcd;
     const dim3 grid((unsigned)(a.slots * kXcds)), block(kThreads);
-    const bool tail = (K % kTileK) != 0;
+    const bool tail = ((w_bits == 16 ? 2 * K : K) % kTileK) != 0;  // (in bytes of an activation row)
     const bool generic = (N % 8) != 0 || acc_out != nullptr || N >= (1 << 21);
 #define VQ_LAUNCH_GEMM(BITS, TAIL, GEN) \
     hipLaunchKernelGGL((gemm_i8_dequant<BITS, TAIL, GEN>), grid, block, 0, stream, a)
     if (w_bits == 8) {
         if (tail) { if (generic) VQ_LAUNCH_GEMM(8, true, true); else VQ_LAUNCH_GEMM(8, true, false); }
         else      { if (generic) VQ_LAUNCH_GEMM(8, false, true); else VQ_LAUNCH_GEMM(8, false, false); }
+    } else if (w_bits == 16) {
+        if (tail) { if (generic) VQ_LAUNCH_GEMM(16, true, true); else VQ_LAUNCH_GEMM(16, true, false); }
+        else      { if (generic) VQ_LAUNCH_GEMM(16, false, true); else VQ_LAUNCH_GEMM(16, false, false); }
     } else {
         if (tail) { if (generic) VQ_LAUNCH_GEMM(4, true, true); else VQ_LAUNCH_GEMM(4, true, false); }
         else      { if (generic) VQ_LAUNCH_GEMM(4, false, true); else VQ_LAUNCH_GEMM(4, false, false); }

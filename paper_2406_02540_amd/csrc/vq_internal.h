@@ -20,10 +20,14 @@ hipError_t launch_residual_quantize(const void* x_f16, const void* y_f16, const 
                                     int tokens_per_sample, void* r_f16, const float* chan_mul, int8_t* xq,
                                     float* x_scale, int M, int K, hipStream_t stream);
 
+hipError_t launch_quantize_static(const void* x_f16, const float* chan_mul, float inv_scale, int8_t* xq,
+                                  int M, int K, hipStream_t stream);
+
 hipError_t launch_quantize_weight(const float* w, const float* chan_s, int w_bits, void* wq_out,
                                   float* w_scale, int N, int K, hipStream_t stream);
 
-// w_bits 8: w is int8 [N,K]; 4: w is packed nibbles [N,K/2].  num_cus: compute units of
+// w_bits 8: w is int8 [N,K]; 4: w is packed nibbles [N,K/2]; 16: the fp16 comparison layer, xq and w
+// are fp16 [M,K] and [N,K], x_scale and w_scale are not read, acc_out must be null.  num_cus: compute units of
 // the device the stream belongs to (the kernel is persistent, one workgroup per CU).
 hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, int w_bits,
                        const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out,

@@ -79,6 +79,39 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_tokens_generic(
     }
 }
 
+// Static quantizer (the comparison point: one scale for the whole tensor, fixed beforehand):
+// element-wise, 8 values per thread where the rows are whole 16-byte chunks.
+template <bool VEC>
+__global__ __launch_bounds__(kQuantThreads) void quantize_static_elems(
+    const _Float16* __restrict__ x, const float* __restrict__ chan_mul, float inv, int8_t* __restrict__ xq,
+    long total, int K) {
+    const long step = (long)gridDim.x * kQuantThreads;
+    if (VEC) {
+        const int K8 = K / 8;
+        for (long c = (long)blockIdx.x * kQuantThreads + threadIdx.x; c < total / 8; c += step) {
+            const half8 v = __builtin_nontemporal_load((const half8*)x + c);
+            const int k = (int)(c % K8) * 8;
+            int q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float t = (float)v[j];
+                if (chan_mul) t = t * chan_mul[k + j];
+                q[j] = quantize_one(t, inv, 127.0f);
+            }
+            int2v o;
+            o.x = pack4(q[0], q[1], q[2], q[3]);
+            o.y = pack4(q[4], q[5], q[6], q[7]);
+            ((int2v*)xq)[c] = o;
+        }
+    } else {
+        for (long e = (long)blockIdx.x * kQuantThreads + threadIdx.x; e < total; e += step) {
+            float t = (float)x[e];
+            if (chan_mul) t = t * chan_mul[e % K];
+            xq[e] = (int8_t)quantize_one(t, inv, 127.0f);
+        }
+    }
+}
+
 // Offline weight quantizer: one workgroup per output channel, fp32 input.
 // BITS == 4 writes two nibbles per byte (k even in bits 0..3, k odd in 4..7).
 template <int BITS, bool HAS_S>
@@ -174,6 +207,22 @@ hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, i
     else
         hipLaunchKernelGGL((quantize_tokens_generic<false>), grid, block, 0, stream,
                            (const _Float16*)x_f16, (const float*)nullptr, xq, x_scale, K);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_static(const void* x_f16, const float* chan_mul, float inv_scale, int8_t* xq,
+                                  int M, int K, hipStream_t stream) {
+    const long total = (long)M * K;
+    const bool vec = (K % 8 == 0);
+    const long work = vec ? total / 8 : total;
+    const long blocks = (work + kQuantThreads - 1) / kQuantThreads;
+    const dim3 grid((unsigned)(blocks < 16384 ? (blocks < 1 ? 1 : blocks) : 16384)), block(kQuantThreads);
+    if (vec)
+        hipLaunchKernelGGL((quantize_static_elems<true>), grid, block, 0, stream, (const _Float16*)x_f16,
+                           chan_mul, inv_scale, xq, total, K);
+    else
+        hipLaunchKernelGGL((quantize_static_elems<false>), grid, block, 0, stream, (const _Float16*)x_f16,
+                           chan_mul, inv_scale, xq, total, K);
     return hipGetLastError();
 }
 
