@@ -52,6 +52,8 @@ def _load():
         lib.oracle_gelu.argtypes = [p, ci, p, i64, i64]
         lib.oracle_layernorm_modulate.argtypes = [p, p, p, i64, ctypes.c_double, p, i64, i64]
         lib.oracle_residual.argtypes = [p, p, p, i64, p, i64, i64]
+        lib.oracle_hadamard_rotate.argtypes = [p, p, i64, p, p, i64, i64]
+        lib.oracle_rotate_weight.argtypes = [p, p, i64, p, p, i64, i64]
         lib.oracle_gemm_f16.argtypes = [p, p, p, p, i64, i64, i64]
         lib.oracle_quantize_static.argtypes = [p, p, ctypes.c_float, p, i64, i64]
         lib.oracle_quantize_weight.argtypes = [p, p, ci, p, p, i64, i64]
@@ -60,7 +62,7 @@ def _load():
         lib.oracle_gemm_i8.argtypes = [p, p, p, i64, i64, i64]
         lib.oracle_dequant.argtypes = [p, p, p, p, p, i64, i64]
         lib.oracle_linear.argtypes = [p, p, p, ci, p, p, p, p, p, p, p, i64, i64, i64]
-        for name in ("oracle_gemm_f16", "oracle_quantize_static", "oracle_quantize_rows_f32", "oracle_gelu", "oracle_layernorm_modulate",
+        for name in ("oracle_hadamard_rotate", "oracle_rotate_weight", "oracle_gemm_f16", "oracle_quantize_static", "oracle_quantize_rows_f32", "oracle_gelu", "oracle_layernorm_modulate",
                      "oracle_residual",
                      "oracle_quantize_per_token", "oracle_quantize_weight", "oracle_pack_int4",
                      "oracle_unpack_int4", "oracle_gemm_i8", "oracle_dequant", "oracle_linear"):
@@ -195,6 +197,39 @@ def residual_quantize(x_f16, y_f16, gate=None, tokens_per_sample=None, chan_mul=
     """Residual add fused with the quantizer: returns (r fp16, xq, x_scale)."""
     r = residual(x_f16, y_f16, gate, tokens_per_sample)
     return (r,) + quantize_per_token(r, chan_mul)
+
+
+HADAMARD_BLOCK = 128
+
+
+def hadamard_rotate(x_f16, chan_mul=None, block: int = HADAMARD_BLOCK):
+    """(X * chan_mul) Q with Q block diagonal, blocks H_block / sqrt(block): fp16 [M,K] -> fp32 [M,K]."""
+    xb = _f16(x_f16)
+    M, K = xb.shape
+    cm = None if chan_mul is None else _arr(chan_mul, np.float32, (K,))
+    t = np.empty((M, K), np.float32)
+    scratch = np.empty((M, K), np.float64)
+    _check(_load().oracle_hadamard_rotate(_ptr(xb), _ptr(cm), int(block), _ptr(t), _ptr(scratch), M, K),
+           "hadamard_rotate")
+    return t
+
+
+def rotate_weight(w_f32, chan_s=None, block: int = HADAMARD_BLOCK):
+    """(W * s) Q, the weight side of the same rotation: fp32 [N,K] -> fp32 [N,K]."""
+    w = _arr(w_f32, np.float32)
+    N, K = w.shape
+    s = None if chan_s is None else _arr(chan_s, np.float32, (K,))
+    out = np.empty((N, K), np.float32)
+    scratch = np.empty((N, K), np.float64)
+    _check(_load().oracle_rotate_weight(_ptr(w), _ptr(s), int(block), _ptr(out), _ptr(scratch), N, K),
+           "rotate_weight")
+    return out
+
+
+def hadamard_quantize(x_f16, chan_mul=None, block: int = HADAMARD_BLOCK):
+    """Scaling, rotation, per-token quantization: returns (t fp32, xq, x_scale)."""
+    t = hadamard_rotate(x_f16, chan_mul, block)
+    return (t,) + quantize_rows_f32(t, None)
 
 
 def gemm_f16(x_f16, w_f16, bias_f16=None):

@@ -47,6 +47,16 @@
  *     rounded), narrowed to fp16 as the new residual stream, and that fp16 row is
  *     quantized.
  *
+ *   - rotation-based balancing, the "dynamic" half of Sec. 4.2: Y = X W^T =
+ *     (X Q)(W Q)^T for an orthogonal Q; the paper takes a Hadamard matrix and
+ *     fuses the transform with the quantizer (Sec. 5.1).  It does not say how a
+ *     channel count that is not a power of two (1152 = 9 * 128) is handled;
+ *     here Q is block diagonal with blocks H_B / sqrt(B), H_B the Sylvester
+ *     Hadamard matrix H[k][c] = (-1)^popcount(k & c) in natural order, B = 128
+ *     (or any power of two that divides K).  Scaling comes first, then the
+ *     rotation: t = ((x * chan_mul) Q) for activations, (w * s) Q for weights.
+ *     fp64 throughout, one rounding to fp32 at the end.
+ *
  * Matrices are dense row-major: X[M,K], W[N,K] (K contiguous), Y[M,N].
  * fp16 values travel as uint16_t bit patterns.
  *
@@ -355,6 +365,60 @@ int oracle_dequant(const int32_t* acc, const float* x_scale, const float* w_scal
             if (bias_f16) yf = yf + oracle_half_to_float(bias_f16[n]);
             y_f16[m * N + n] = oracle_float_to_half(yf);
         }
+    return ORACLE_OK;
+}
+
+/* ---- rotation-based balancing (Sec. 4.2), block-diagonal Hadamard matrix ---------- */
+
+static int parity_of(uint64_t v) { /* popcount mod 2 */
+    int p = 0;
+    while (v) { p ^= 1; v &= v - 1; }
+    return p;
+}
+
+/* rows [M,K] (fp64 values supplied by get(m,k)) times Q, written out as fp32. */
+static void rotate_rows(const double* in, float* out, int64_t M, int64_t K, int64_t B) {
+    const double norm = 1.0 / sqrt((double)B);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t b0 = 0; b0 < K; b0 += B) {
+            for (int64_t c = 0; c < B; ++c) {
+                double sum = 0.0;
+                for (int64_t k = 0; k < B; ++k) {
+                    const double v = in[m * K + b0 + k];
+                    sum += parity_of((uint64_t)(k & c)) ? -v : v;
+                }
+                out[m * K + b0 + c] = (float)(sum * norm);
+            }
+        }
+    }
+}
+
+static int bad_block(int64_t K, int64_t B) { return B <= 0 || (B & (B - 1)) != 0 || K % B != 0; }
+
+/* Activations: t[m,:] = (float(x[m,:]) * chan_mul) Q, block size B. `scratch` is M*K doubles. */
+int oracle_hadamard_rotate(const uint16_t* x_f16, const float* chan_mul, int64_t B, float* t_f32,
+                           double* scratch, int64_t M, int64_t K) {
+    if (!x_f16 || !t_f32 || !scratch || M < 0 || K <= 0 || bad_block(K, B)) return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < M * K; ++i) {
+        double v = (double)oracle_half_to_float(x_f16[i]);
+        if (chan_mul) v = v * (double)chan_mul[i % K];
+        scratch[i] = v;
+    }
+    rotate_rows(scratch, t_f32, M, K, B);
+    return ORACLE_OK;
+}
+
+/* Weights: w'[n,:] = (w[n,:] * s) Q, the counterpart that keeps X W^T unchanged. */
+int oracle_rotate_weight(const float* w, const float* chan_s, int64_t B, float* w_rot,
+                         double* scratch, int64_t N, int64_t K) {
+    if (!w || !w_rot || !scratch || N < 0 || K <= 0 || bad_block(K, B)) return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < N * K; ++i) {
+        double v = (double)w[i];
+        if (chan_s) v = v * (double)chan_s[i % K];
+        scratch[i] = v;
+    }
+    rotate_rows(scratch, w_rot, N, K, B);
     return ORACLE_OK;
 }
 

@@ -253,3 +253,83 @@ def test_quantize_static_against_numpy_and_error_bound(oracle):
     err = np.abs(got.astype(np.float64) * float(scale) - t)
     assert np.all(err[inside] <= 0.5 * float(scale) * (1 + 2.0 ** -15))
     assert np.all(np.abs(got[~inside]) == 127)
+
+
+# ---- rotation-based balancing: block-diagonal Hadamard matrix (Sec. 4.2) ----------------
+
+def _q_matrix(K, B):
+    from scipy.linalg import hadamard  # Sylvester construction, natural order
+    q = np.zeros((K, K))
+    for b0 in range(0, K, B):
+        q[b0:b0 + B, b0:b0 + B] = hadamard(B) / np.sqrt(B)
+    return q
+
+
+@pytest.mark.parametrize("K,B", [(128, 128), (384, 128), (64, 16), (96, 32)])
+def test_hadamard_rotate_against_scipy_matrix(oracle, K, B):
+    g = np.random.default_rng(31)
+    x = (g.standard_normal((5, K)) * 3).astype(np.float16)
+    cm = np.exp(g.uniform(-1, 1, K)).astype(np.float32)
+    q = _q_matrix(K, B)
+    for mul in (None, cm):
+        xs = x.astype(np.float64) * (1.0 if mul is None else mul.astype(np.float64))
+        want = xs @ q
+        got = oracle.hadamard_rotate(x, mul, B).astype(np.float64)
+        assert np.all(np.abs(got - want) <= np.abs(np.spacing(want.astype(np.float32))) + 1e-12)
+
+
+def test_hadamard_rotate_closed_forms(oracle):
+    B = 128
+    # a unit pulse at channel k becomes row k of H / sqrt(B): all magnitudes equal, signs (-1)^popcount(k & c)
+    x = np.zeros((3, 2 * B), np.float16)
+    x[0, 0] = 1; x[1, 1] = 1; x[2, B + 5] = 2
+    t = oracle.hadamard_rotate(x, None, B).astype(np.float64)
+    r = 1 / np.sqrt(B)
+    assert np.allclose(t[0, :B], r) and not t[0, B:].any()
+    assert np.allclose(t[1, :B], r * np.where(np.arange(B) & 1, -1, 1))
+    signs = np.array([(-1) ** bin(5 & c).count("1") for c in range(B)])
+    assert np.allclose(t[2, B:], 2 * r * signs) and not t[2, :B].any()
+    # a constant block has only its first (mean) component: sqrt(B) times the constant
+    x = np.full((1, B), 0.5, np.float16)
+    t = oracle.hadamard_rotate(x, None, B)[0]
+    assert np.isclose(t[0], 0.5 * np.sqrt(B)) and np.allclose(t[1:], 0, atol=1e-7)
+
+
+def test_hadamard_is_orthogonal_and_its_own_inverse(oracle):
+    g = np.random.default_rng(32)
+    K = 256
+    w = g.standard_normal((7, K)).astype(np.float32)
+    r1 = oracle.rotate_weight(w, None, 128)
+    assert np.allclose((r1.astype(np.float64) ** 2).sum(axis=1), (w.astype(np.float64) ** 2).sum(axis=1), rtol=1e-6)
+    r2 = oracle.rotate_weight(r1, None, 128)   # H is symmetric and H H = B I
+    assert np.allclose(r2, w, rtol=0, atol=3e-6)
+
+
+def test_rotation_leaves_the_product_unchanged(oracle):
+    # Sec. 4.2: Y = X W^T = (X Q)(W Q)^T, here together with the scaling of Eq. 3
+    g = np.random.default_rng(33)
+    M, N, K = 6, 9, 384
+    x = g.standard_normal((M, K)).astype(np.float16)
+    w = (g.standard_normal((N, K)) * 0.05).astype(np.float32)
+    s = np.exp(g.uniform(np.log(0.25), np.log(4), K)).astype(np.float32)
+    cm = (np.float32(1.0) / s).astype(np.float32)
+    xr = oracle.hadamard_rotate(x, cm, 128).astype(np.float64)
+    wr = oracle.rotate_weight(w, s, 128).astype(np.float64)
+    want = (x.astype(np.float64) * cm.astype(np.float64)) @ (w.astype(np.float64) * s.astype(np.float64)).T
+    assert np.allclose(xr @ wr.T, want, rtol=0, atol=2e-5 * np.abs(want).max())
+
+
+def test_rotation_spreads_an_outlier_channel(oracle):
+    # what the rotation is for: one channel 100 times larger than the rest becomes a flat block
+    g = np.random.default_rng(34)
+    x = g.standard_normal((4, 128)).astype(np.float32)
+    x[:, 17] *= 100
+    x = x.astype(np.float16)
+    t = oracle.hadamard_rotate(x, None, 128)
+    before = np.abs(x.astype(np.float32)).max(axis=1) / np.sqrt((x.astype(np.float32) ** 2).mean(axis=1))
+    after = np.abs(t).max(axis=1) / np.sqrt((t ** 2).mean(axis=1))
+    assert np.all(before > 8) and np.all(after < 2)
+    _, q, s = oracle.hadamard_quantize(x, None, 128)
+    assert np.all(np.abs(q).max(axis=1) == 127)
+    with pytest.raises(oracle.OracleError):
+        oracle.hadamard_rotate(x, None, 96)
