@@ -210,6 +210,9 @@ def main():
                 r = torch.empty_like(L["x"])
                 yb = (L["x"].float() * 0.25).half()
                 runs = [("residual_quantize", 7, lambda: vq.vq_residual_quantize(L["x"], yb, mod[0], T, r, L["cm"], xq=L["xq"], x_scale=L["xs"]))]
+            elif s.name == "qkv":
+                runs = [("layernorm_quantize", 3, lambda: vq.vq_layernorm_quantize(L["x"], mod[0], mod[1], T, 1e-6, L["cm"], xq=L["xq"], x_scale=L["xs"])),
+                        ("hadamard_quantize", 3, lambda: vq.vq_hadamard_quantize(L["x"], L["cm"], xq=L["xq"], x_scale=L["xs"]))]
             else:
                 runs = [("layernorm_quantize", 3, lambda: vq.vq_layernorm_quantize(L["x"], mod[0], mod[1], T, 1e-6, L["cm"], xq=L["xq"], x_scale=L["xs"]))]
             for name, bpe, fn in runs:

@@ -52,6 +52,7 @@ typedef enum vq_status {
 
 #define VQ_MAX_K 131072
 #define VQ_MAX_FUSED_K 8192 /* the fused quantizers keep a token in registers */
+#define VQ_HADAMARD_BLOCK 128 /* block size of the rotation */
 
 /*
  * Dynamic per-token activation quantizer (Sec. 4.1 "Fine-grained Grouping and
@@ -108,6 +109,26 @@ int vq_layernorm_quantize(const void* x_f16, const float* mod_scale, const float
 int vq_residual_quantize(const void* x_f16, const void* y_f16, const float* gate, int tokens_per_sample,
                          void* r_f16, const float* chan_mul, int8_t* xq, float* x_scale, int M, int K,
                          void* hip_stream);
+
+/*
+ * Rotation-based channel balancing, the "dynamic" half of the static-dynamic balancing of
+ * Sec. 4.2 (Y = X W^T = (X Q)(W Q)^T for an orthogonal Q; the scaling of Eq. 3 comes first),
+ * with the Hadamard transform fused into the quantizer as in Sec. 5.1.  Q is block diagonal
+ * with blocks H_128 / sqrt(128), H_128 the Sylvester Hadamard matrix in natural order
+ * (H[k][c] = (-1)^popcount(k & c)); the paper does not say how channel counts that are not a
+ * power of two (1152, 4608) are rotated, blocks of 128 are this library's reading.
+ *
+ * vq_hadamard_quantize: t[m,:] = (float(x[m,:]) * chan_mul) Q, then the per-token quantizer
+ *                       of vq_quantize_per_token on t.  K % 128 == 0, K <= VQ_MAX_FUSED_K.
+ *                       fp32 butterflies: as for the fused LayerNorm and GELU the codes are
+ *                       determined up to the rounding of t (a few fp32 ulps).
+ * vq_rotate_weight:     the weight side, offline: w_rot[n,:] = (w[n,:] * chan_s) Q in fp32, to
+ *                       be quantized with vq_quantize_weight (chan_s = NULL there).  w_f32 and
+ *                       w_rot_f32 are fp32 [N,K] and may be the same buffer.
+ */
+int vq_hadamard_quantize(const void* x_f16, const float* chan_mul, int8_t* xq, float* x_scale, int M, int K,
+                         void* hip_stream);
+int vq_rotate_weight(const float* w_f32, const float* chan_s, float* w_rot_f32, int N, int K, void* hip_stream);
 
 /*
  * The two comparison points of the paper's hardware evaluation (Sec. 5.3 "Hardware

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     VqError,
     vq_gelu_quantize,
     vq_gemm_f16,
+    vq_hadamard_quantize,
     vq_gemm_w4a8,
     vq_gemm_w8a8,
     vq_layernorm_quantize,
@@ -16,4 +17,5 @@ from .binding import (  # noqa: F401
     vq_quantize_static,
     vq_quantize_weight,
     vq_residual_quantize,
+    vq_rotate_weight,
 )

@@ -26,6 +26,8 @@ SIGNATURES = {
     "vq_gelu_quantize": (_I, [_P, _I, _P, _P, _P, _I, _I, _P]),
     "vq_layernorm_quantize": (_I, [_P, _P, _P, _I, ctypes.c_float, _P, _P, _P, _I, _I, _P]),
     "vq_residual_quantize": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _I, _I, _P]),
+    "vq_hadamard_quantize": (_I, [_P, _P, _P, _P, _I, _I, _P]),
+    "vq_rotate_weight": (_I, [_P, _P, _P, _I, _I, _P]),
     "vq_gemm_f16": (_I, [_P, _P, _P, _P, _I, _I, _I, _P]),
     "vq_quantize_static": (_I, [_P, _P, ctypes.c_float, _P, _I, _I, _P]),
     "vq_gemm_w8a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
@@ -177,6 +179,32 @@ def vq_residual_quantize(x, y, gate=None, tokens_per_sample=None, r=None, chan_m
     _check(lib().vq_residual_quantize(_ptr(x), _ptr(y), _ptr(gate), T, _ptr(r), _ptr(chan_mul), _ptr(xq),
                                       _ptr(x_scale), M, K, _stream(stream)), "vq_residual_quantize")
     return r, xq, x_scale
+
+
+def vq_hadamard_quantize(x, chan_mul=None, xq=None, x_scale=None, stream=None):
+    """Scaling, block Hadamard rotation, per-token quantizer: x fp16 [M,K] -> (xq, x_scale)."""
+    x = _dev(x, torch.float16, "x")
+    M, K = x.shape
+    chan_mul, xq, x_scale = _quant_outputs(x, chan_mul, xq, x_scale)
+    _check(lib().vq_hadamard_quantize(_ptr(x), _ptr(chan_mul), _ptr(xq), _ptr(x_scale), M, K, _stream(stream)),
+           "vq_hadamard_quantize")
+    return xq, x_scale
+
+
+def vq_rotate_weight(w, chan_s=None, out=None, stream=None):
+    """Weight side of the rotation: w fp32 [N,K] (* chan_s) -> fp32 [N,K]."""
+    w = _dev(w, torch.float32, "w")
+    N, K = w.shape
+    chan_s = _dev(chan_s, torch.float32, "chan_s")
+    if chan_s is not None and tuple(chan_s.shape) != (K,):
+        raise ValueError("chan_s must have shape [K]")
+    if out is None:
+        out = torch.empty_like(w)
+    _dev(out, torch.float32, "out")
+    if tuple(out.shape) != (N, K):
+        raise ValueError("out must have the shape of w")
+    _check(lib().vq_rotate_weight(_ptr(w), _ptr(chan_s), _ptr(out), N, K, _stream(stream)), "vq_rotate_weight")
+    return out
 
 
 def vq_gemm_f16(x, w, bias=None, y=None, stream=None):

@@ -124,6 +124,28 @@ int vq_gelu_quantize(const void* h_f16, int approximate, const float* chan_mul, 
                                                   (hipStream_t)hip_stream));
 }
 
+int vq_hadamard_quantize(const void* x_f16, const float* chan_mul, int8_t* xq, float* x_scale, int M, int K,
+                         void* hip_stream) {
+    const int v = validate_fused(x_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    if (K % VQ_HADAMARD_BLOCK != 0) return VQ_ERR_SHAPE;
+    if (M == 0) return VQ_OK;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_hadamard_quantize(x_f16, chan_mul, xq, x_scale, M, K,
+                                                      (hipStream_t)hip_stream));
+}
+
+int vq_rotate_weight(const float* w_f32, const float* chan_s, float* w_rot_f32, int N, int K, void* hip_stream) {
+    if (N < 0 || K <= 0 || K > VQ_MAX_FUSED_K || K % VQ_HADAMARD_BLOCK != 0) return VQ_ERR_SHAPE;
+    if (N == 0) return VQ_OK;
+    if (!w_f32 || !w_rot_f32) return VQ_ERR_NULL;
+    if (misaligned(w_f32) || misaligned(w_rot_f32) || (chan_s && misaligned(chan_s))) return VQ_ERR_ALIGN;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_rotate_weight(w_f32, chan_s, w_rot_f32, N, K, (hipStream_t)hip_stream));
+}
+
 int vq_layernorm_quantize(const void* x_f16, const float* mod_scale, const float* mod_shift,
                           int tokens_per_sample, float eps, const float* chan_mul, int8_t* xq,
                           float* x_scale, int M, int K, void* hip_stream) {

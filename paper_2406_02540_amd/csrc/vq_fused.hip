@@ -21,7 +21,7 @@
 namespace vq {
 namespace {
 
-enum Producer { kGeluErf = 0, kGeluTanh = 1, kLayerNorm = 2, kResidual = 3 };
+enum Producer { kGeluErf = 0, kGeluTanh = 1, kLayerNorm = 2, kResidual = 3, kHadamard = 4 };
 
 struct FusedArgs {
     const half8* x;          // [M,K8] the producer's input
@@ -53,6 +53,32 @@ __device__ __forceinline__ float gelu_tanh(float x) {
     return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// The value of the lane whose index differs in one bit (1, 2, 4 or 8), as data movement
+// inside a row of 16 lanes: DPP quad permutes for 1 and 2, ds_swizzle (bit mode) for 4 and 8.
+template <int MASK>
+__device__ __forceinline__ float from_lane_xor(float v) {
+    const int iv = __builtin_bit_cast(int, v);
+    int r;
+    if (MASK == 1) r = __builtin_amdgcn_mov_dpp(iv, 0xB1, 0xF, 0xF, true);       // quad_perm [1,0,3,2]
+    else if (MASK == 2) r = __builtin_amdgcn_mov_dpp(iv, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+    else r = __builtin_amdgcn_ds_swizzle(iv, (MASK << 10) | 0x1F);               // and 0x1F, or 0, xor MASK
+    return __builtin_bit_cast(float, r);
+}
+
+// One stage of the Walsh-Hadamard transform across lanes: index bit MASK of the lane.
+// The lane with the bit clear gets a + b, the one with it set a - b (a = the clear lane's value).
+template <int MASK, int NCH>
+__device__ __forceinline__ void hadamard_lane_stage(float (&t)[NCH][8], int sub) {
+    const int sign = (sub & MASK) ? (int)0x80000000 : 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float other = from_lane_xor<MASK>(t[i][j]);
+            t[i][j] = other + __builtin_bit_cast(float, __builtin_bit_cast(int, t[i][j]) ^ sign);
+        }
+}
+
 template <int PRODUCER, int NCH, int LANES>
 __global__ __launch_bounds__(kQuantThreads) void produce_quantize_tokens(const FusedArgs a) {
     const RowLane<LANES> rl(a.M);
@@ -62,6 +88,47 @@ __global__ __launch_bounds__(kQuantThreads) void produce_quantize_tokens(const F
 
     float t[NCH][8];
     load_row<NCH, LANES>(a.x + row_off, rl.row_ok, rl.sub, K8, t);
+
+    if (PRODUCER == kHadamard) {
+        // Rotation-based balancing (Sec. 4.2): t = (x * chan_mul) Q with Q block diagonal,
+        // blocks H_128 / sqrt(128).  A block is 16 consecutive chunks = the 16 lanes sub%16 of a
+        // token with one chunk index i, so element 8 (sub%16) + j of the block sits in lane
+        // sub, register t[i][j]: three butterfly stages inside the registers, four across lanes.
+        if (a.chan_mul) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const int c = i * LANES + rl.sub;
+                if (rl.row_ok && c < K8) {
+                    const float4v m0 = a.chan_mul[2 * c], m1 = a.chan_mul[2 * c + 1];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        t[i][j] = t[i][j] * m0[j];
+                        t[i][4 + j] = t[i][4 + j] * m1[j];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+#pragma unroll
+            for (int bit = 1; bit < 8; bit <<= 1)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (!(j & bit)) {
+                        const float lo = t[i][j], hi = t[i][j | bit];
+                        t[i][j] = lo + hi;
+                        t[i][j | bit] = lo - hi;
+                    }
+        }
+        hadamard_lane_stage<1>(t, rl.sub);
+        hadamard_lane_stage<2>(t, rl.sub);
+        hadamard_lane_stage<4>(t, rl.sub);
+        hadamard_lane_stage<8>(t, rl.sub);
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[i][j] = t[i][j] * 0.08838834764831845f;  // 1 / sqrt(128)
+    }
 
     if (PRODUCER == kGeluErf || PRODUCER == kGeluTanh) {
 #pragma unroll
@@ -157,10 +224,36 @@ __global__ __launch_bounds__(kQuantThreads) void produce_quantize_tokens(const F
         }
     }
 
-    if (a.chan_mul)
+    if (PRODUCER != kHadamard && a.chan_mul)  // (the rotation has the scaling before itself)
         fold_quantize_store<NCH, LANES, true>(t, a.chan_mul, rl.row_ok, rl.sub, K8, rl.m, a.xq, a.x_scale);
     else
         fold_quantize_store<NCH, LANES, false>(t, a.chan_mul, rl.row_ok, rl.sub, K8, rl.m, a.xq, a.x_scale);
+}
+
+// Weight side of the rotation, offline: one workgroup per output channel, the row in LDS,
+// seven butterfly stages per block of 128 with a barrier after each.
+__global__ __launch_bounds__(kQuantThreads) void rotate_weight_rows(const float* __restrict__ w,
+                                                                    const float* __restrict__ chan_s,
+                                                                    float* __restrict__ out, int K) {
+    __shared__ float row[8192];
+    const long n = blockIdx.x;
+    for (int k = threadIdx.x; k < K; k += kQuantThreads) {
+        float v = w[n * K + k];
+        if (chan_s) v = v * chan_s[k];
+        row[k] = v;
+    }
+    __syncthreads();
+    for (int bit = 1; bit < 128; bit <<= 1) {
+        for (int p = threadIdx.x; p < K / 2; p += kQuantThreads) {
+            // pair p: insert a zero at position `bit` of the index
+            const int lo = ((p & ~(bit - 1)) << 1) | (p & (bit - 1));
+            const float a0 = row[lo], a1 = row[lo | bit];
+            row[lo] = a0 + a1;
+            row[lo | bit] = a0 - a1;
+        }
+        __syncthreads();
+    }
+    for (int k = threadIdx.x; k < K; k += kQuantThreads) out[n * K + k] = row[k] * 0.08838834764831845f;
 }
 
 template <int PRODUCER, int NCH, int LANES>
@@ -204,6 +297,25 @@ hipError_t launch_gelu_quantize(const void* h_f16, int approximate, const float*
     a.K8 = K / 8;
     a.tokens_per_sample = 1;
     return approximate ? launch_producer<kGeluTanh>(a, stream) : launch_producer<kGeluErf>(a, stream);
+}
+
+hipError_t launch_hadamard_quantize(const void* x_f16, const float* chan_mul, int8_t* xq, float* x_scale,
+                                    int M, int K, hipStream_t stream) {
+    FusedArgs a{};
+    a.x = (const half8*)x_f16;
+    a.chan_mul = (const float4v*)chan_mul;
+    a.xq = (int2v*)xq;
+    a.x_scale = x_scale;
+    a.M = M;
+    a.K8 = K / 8;
+    a.tokens_per_sample = 1;
+    return launch_producer<kHadamard>(a, stream);
+}
+
+hipError_t launch_rotate_weight(const float* w, const float* chan_s, float* w_rot, int N, int K,
+                                hipStream_t stream) {
+    hipLaunchKernelGGL(rotate_weight_rows, dim3((unsigned)N), dim3(kQuantThreads), 0, stream, w, chan_s, w_rot, K);
+    return hipGetLastError();
 }
 
 hipError_t launch_layernorm_quantize(const void* x_f16, const float* mod_scale, const float* mod_shift,

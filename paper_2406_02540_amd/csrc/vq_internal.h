@@ -13,6 +13,10 @@ hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, i
 // The quantizer fused behind its producer (vq_fused.hip): K % 8 == 0, K <= 8192.
 hipError_t launch_gelu_quantize(const void* h_f16, int approximate, const float* chan_mul, int8_t* xq,
                                 float* x_scale, int M, int K, hipStream_t stream);
+hipError_t launch_hadamard_quantize(const void* x_f16, const float* chan_mul, int8_t* xq, float* x_scale,
+                                    int M, int K, hipStream_t stream);  // K % 128 == 0
+hipError_t launch_rotate_weight(const float* w, const float* chan_s, float* w_rot, int N, int K,
+                                hipStream_t stream);                  // K % 128 == 0, K <= 8192
 hipError_t launch_layernorm_quantize(const void* x_f16, const float* mod_scale, const float* mod_shift,
                                      int tokens_per_sample, float eps, const float* chan_mul, int8_t* xq,
                                      float* x_scale, int M, int K, hipStream_t stream);

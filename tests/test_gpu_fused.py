@@ -188,3 +188,72 @@ def test_full_size_layernorm_feeds_qkv_and_residual_feeds_it(vq, oracle):
     q, s = vq.vq_layernorm_quantize(r, dev(sc), dev(sh), T, 1e-6)
     torch.cuda.synchronize()
     check_valid(host(q), host(s), t, None, q_ref, s_ref, min_equal=0.999)
+
+
+# ---- rotation-based balancing: block Hadamard transform fused with the quantizer (Sec. 4.2) ----
+
+HADAMARD_SHAPES = [(1, 128), (5, 256), (37, 1152), (130, 4608), (7, 4096), (3, 8192), (9, 2176), (1000, 1152)]
+
+
+@pytest.mark.parametrize("M,K", HADAMARD_SHAPES)
+@pytest.mark.parametrize("with_mul", [False, True])
+def test_hadamard_quantize(vq, oracle, M, K, with_mul):
+    say(f"hadamard_quantize M={M} K={K} mul={with_mul}")
+    x, g = rows(400 + M + K, M, K)
+    x[:, g.integers(0, K, max(1, K // 100))] *= np.float16(30)  # outlier channels: what the rotation is for
+    if M > 2:
+        x[1] = 0
+    cm = np.exp(g.uniform(np.log(0.25), np.log(4), K)).astype(np.float32) if with_mul else None
+    t, q_ref, s_ref = oracle.hadamard_quantize(x, cm)
+    q, s = vq.vq_hadamard_quantize(dev(x), dev(cm))
+    torch.cuda.synchronize()
+    check_valid(host(q), host(s), t, None, q_ref, s_ref)
+
+
+def test_rotate_weight_and_rotated_layer(vq, oracle):
+    g = np.random.default_rng(4545)
+    M, N, K = 300, 264, 1152
+    x = g.standard_normal((M, K)).astype(np.float32)
+    x[:, g.integers(0, K, 12)] *= 50          # time-varying outlier channels
+    x = x.astype(np.float16)
+    w = (g.standard_normal((N, K)) * 0.02).astype(np.float32)
+    s = np.exp(g.uniform(np.log(0.5), np.log(2), K)).astype(np.float32)
+    cm = (np.float32(1) / s).astype(np.float32)
+    b = (g.standard_normal(N) * 0.01).astype(np.float16)
+    # weight side: the GPU rotation against the oracle's (fp32 butterflies against fp64 sums)
+    w_rot_ref = oracle.rotate_weight(w, s)
+    w_rot = vq.vq_rotate_weight(dev(w), dev(s))
+    torch.cuda.synchronize()
+    norm = np.sqrt((w_rot_ref.astype(np.float64) ** 2).reshape(N, K // 128, 128).sum(axis=2)).repeat(128, axis=1)
+    assert np.all(np.abs(host(w_rot).astype(np.float64) - w_rot_ref) <= 1e-6 * norm + 1e-12)
+    # the whole rotated W8A8 layer on the GPU ...
+    wq, ws = vq.vq_quantize_weight(w_rot, None, 8)
+    xq, xs = vq.vq_hadamard_quantize(dev(x), dev(cm))
+    y = vq.vq_gemm_w8a8(xq, xs, wq, ws, dev(b))
+    torch.cuda.synchronize()
+    # ... stays within the rounding-error bound of Eq. 2 around the exact product (Sec. 4.2: the
+    # rotation leaves X W^T unchanged), and is closer to it than the layer without rotation
+    exact = x.astype(np.float64) @ w.astype(np.float64).T + b.astype(np.float64)
+    xr = oracle.hadamard_rotate(x, cm).astype(np.float64)
+    bound = (np.abs(xr) @ np.full((K, 1), 1.0)) * (host(ws).astype(np.float64)[None, :] / 2) \
+        + host(xs).astype(np.float64)[:, None] / 2 * np.abs(w_rot_ref.astype(np.float64)).sum(axis=1)[None, :] \
+        + K * host(xs).astype(np.float64)[:, None] * host(ws).astype(np.float64)[None, :] / 4
+    err_rot = np.abs(host(y).astype(np.float64) - exact)
+    assert np.all(err_rot <= bound + 2.0 ** -10 * np.abs(exact) + 1e-3)
+    wq0, ws0 = vq.vq_quantize_weight(dev(w), dev(s), 8)
+    xq0, xs0 = vq.vq_quantize_per_token(dev(x), dev(cm))
+    y0 = vq.vq_gemm_w8a8(xq0, xs0, wq0, ws0, dev(b))
+    torch.cuda.synchronize()
+    err_plain = np.abs(host(y0).astype(np.float64) - exact)
+    say(f"rms error with rotation {np.sqrt((err_rot ** 2).mean()):.4e}, without {np.sqrt((err_plain ** 2).mean()):.4e}")
+    assert np.sqrt((err_rot ** 2).mean()) < np.sqrt((err_plain ** 2).mean())
+
+
+def test_hadamard_calls_rejected(vq):
+    from paper_2406_02540_amd.binding import VqError
+    x = torch.zeros((4, 192), dtype=torch.float16, device="cuda")  # K not a multiple of 128
+    with pytest.raises(VqError) as e:
+        vq.vq_hadamard_quantize(x)
+    assert e.value.status == 2
+    with pytest.raises(VqError):
+        vq.vq_rotate_weight(torch.zeros((4, 192), device="cuda"))

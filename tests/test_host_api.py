@@ -107,6 +107,29 @@ def test_fused_quantizer_argument_errors(lib):
     assert rs(P(A), P(A), None, 2, P(A), None, P(A), P(A), 4, 64, None) == 6
 
 
+def test_rotation_and_comparison_argument_errors(lib):
+    hq, rw, gf, qs = lib.vq_hadamard_quantize, lib.vq_rotate_weight, lib.vq_gemm_f16, lib.vq_quantize_static
+    F = ctypes.c_float
+    assert hq(P(A), None, P(A), P(A), 4, 192, None) == 2       # K must be whole blocks of 128
+    assert hq(P(A), None, P(A), P(A), 4, 8320, None) == 2      # and fit the registers
+    assert hq(None, None, P(A), P(A), 4, 256, None) == 1
+    assert hq(P(A), P(A + 4), P(A), P(A), 4, 256, None) == 3
+    assert hq(P(A), None, P(A), P(A), 4, 256, None) == 6
+    assert rw(P(A), None, P(A), 4, 200, None) == 2
+    assert rw(None, None, P(A), 4, 256, None) == 1
+    assert rw(P(A), None, P(A + 8), 4, 256, None) == 3
+    assert rw(None, None, None, 0, 256, None) == 0
+    assert gf(P(A), P(A), None, P(A), 4, 8, 12, None) == 2     # K % 8
+    assert gf(P(A), None, None, P(A), 4, 8, 16, None) == 1
+    assert gf(P(A), P(A), P(A + 2), P(A), 4, 8, 16, None) == 3
+    assert gf(None, None, None, None, 0, 8, 16, None) == 0
+    assert gf(P(A), P(A), None, P(A), 4, 8, 16, None) == 6
+    assert qs(P(A), None, F(0.0), P(A), 4, 64, None) == 2
+    assert qs(P(A), None, F(-1.0), P(A), 4, 64, None) == 2
+    assert qs(P(A), None, F(0.5), None, 4, 64, None) == 1
+    assert qs(P(A), None, F(0.5), P(A), 4, 64, None) == 6
+
+
 def test_gemm_argument_errors(lib):
     for g, kmult in ((lib.vq_gemm_w8a8, 16), (lib.vq_gemm_w4a8, 32)):
         ok = [P(A), P(A), P(A), P(A), None, P(A), None]
