@@ -47,17 +47,33 @@ struct RowLane {
 };
 
 // Sum (or maximum) over the LANES lanes of a token; every lane gets the result.
-template <int LANES>
-__device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-    for (int off = LANES / 2; off >= 1; off >>= 1) v = v + __shfl_xor(v, off, kWave);
+// Data moves between lanes without LDS round trips where the hardware allows it: DPP quad
+// permutes (lane ^ 1, lane ^ 2), then the mirrored lane of the other half of 8 and of 16
+// lanes (by then both halves are uniform, so any lane of the other half will do), a
+// ds_swizzle for lane ^ 16 and a permute through LDS only for lane ^ 32.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int LANES, class Op>
+__device__ __forceinline__ float group_reduce(float v, Op op) {
+    static_assert(LANES == 16 || LANES == 32 || LANES == 64, "lane groups are 16, 32 or 64 wide");
+    v = op(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = op(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = op(v, dpp_move<0x141>(v));  // row_half_mirror
+    v = op(v, dpp_move<0x140>(v));  // row_mirror
+    if (LANES >= 32)
+        v = op(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), (16 << 10) | 0x1F)));
+    if (LANES >= 64) v = op(v, __shfl_xor(v, 32, kWave));
     return v;
 }
 template <int LANES>
+__device__ __forceinline__ float group_sum(float v) {
+    return group_reduce<LANES>(v, [](float a, float b) { return a + b; });
+}
+template <int LANES>
 __device__ __forceinline__ float group_max(float v) {
-#pragma unroll
-    for (int off = LANES / 2; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+    return group_reduce<LANES>(v, [](float a, float b) { return fmaxf(a, b); });
 }
 
 // The token's fp16 row -> fp32 registers (chunks past the row, or of a missing token: zeros).
