@@ -22,7 +22,10 @@
 //     travel packed (half the bytes).
 //   - The direct loads are issued from inline assembly and waited for with an
 //     explicit s_waitcnt: the compiler would otherwise wait for all of them
-//     before every LDS read and undo the prefetch.
+//     before every LDS read and undo the prefetch.  They are paced, one load per
+//     two MFMAs over the first half of a stage: the CU's load path takes 64 bytes
+//     per cycle, half of a stage's duration for its 64 KiB, and a wave that
+//     queues there issues no MFMA.
 //   - LDS tiles are [row][128 B] with the eight 16-byte chunks of a row XOR-ed
 //     by (row/2)%8, which makes the 16-lane groups of a ds_read_b128 hit 16
 //     different bank groups.
@@ -48,6 +51,10 @@
 // The epilogue computes fp16_rne(fma_f32(float(acc) * x_scale, w_scale, bias)): one fp32
 // rounding fewer than three separate operations, so an output can differ from the
 // separately rounded value in the last fp16 place.
+//
+// W_BITS == 16 instantiates the same kernel for fp16 operands and fp32 sums
+// (v_mfma_f32_32x32x16_f16, the same 16 bytes of K per lane and operand): the FP16 layer
+// the paper's hardware evaluation compares against (Sec. 5.3), y = fp16(sum + bias).
 #include <type_traits>
 
 #include "vq_gemm_common.h"
