@@ -52,6 +52,9 @@ def _load():
         lib.oracle_gelu.argtypes = [p, ci, p, i64, i64]
         lib.oracle_layernorm_modulate.argtypes = [p, p, p, i64, ctypes.c_double, p, i64, i64]
         lib.oracle_residual.argtypes = [p, p, p, i64, p, i64, i64]
+        lib.oracle_channel_absmax_f16.argtypes = [p, p, i64, i64]
+        lib.oracle_channel_absmax_f32.argtypes = [p, p, i64, i64]
+        lib.oracle_balance_mask.argtypes = [p, p, ctypes.c_double, p, p, i64]
         lib.oracle_hadamard_rotate.argtypes = [p, p, i64, p, p, i64, i64]
         lib.oracle_rotate_weight.argtypes = [p, p, i64, p, p, i64, i64]
         lib.oracle_gemm_f16.argtypes = [p, p, p, p, i64, i64, i64]
@@ -62,7 +65,8 @@ def _load():
         lib.oracle_gemm_i8.argtypes = [p, p, p, i64, i64, i64]
         lib.oracle_dequant.argtypes = [p, p, p, p, p, i64, i64]
         lib.oracle_linear.argtypes = [p, p, p, ci, p, p, p, p, p, p, p, i64, i64, i64]
-        for name in ("oracle_hadamard_rotate", "oracle_rotate_weight", "oracle_gemm_f16", "oracle_quantize_static", "oracle_quantize_rows_f32", "oracle_gelu", "oracle_layernorm_modulate",
+        for name in ("oracle_channel_absmax_f16", "oracle_channel_absmax_f32", "oracle_balance_mask",
+                     "oracle_hadamard_rotate", "oracle_rotate_weight", "oracle_gemm_f16", "oracle_quantize_static", "oracle_quantize_rows_f32", "oracle_gelu", "oracle_layernorm_modulate",
                      "oracle_residual",
                      "oracle_quantize_per_token", "oracle_quantize_weight", "oracle_pack_int4",
                      "oracle_unpack_int4", "oracle_gemm_i8", "oracle_dequant", "oracle_linear"):
@@ -197,6 +201,31 @@ def residual_quantize(x_f16, y_f16, gate=None, tokens_per_sample=None, chan_mul=
     """Residual add fused with the quantizer: returns (r fp16, xq, x_scale)."""
     r = residual(x_f16, y_f16, gate, tokens_per_sample)
     return (r,) + quantize_per_token(r, chan_mul)
+
+
+def channel_absmax(a):
+    """max over the rows of |a| per column: fp16 activations [M,K] or fp32 weights [N,K] -> fp32 [K]."""
+    a = np.ascontiguousarray(a)
+    R, K = a.shape
+    out = np.empty((K,), np.float32)
+    if a.dtype == np.float16:
+        _check(_load().oracle_channel_absmax_f16(_ptr(a.view(np.uint16)), _ptr(out), R, K), "channel_absmax")
+    elif a.dtype == np.float32:
+        _check(_load().oracle_channel_absmax_f32(_ptr(a), _ptr(out), R, K), "channel_absmax")
+    else:
+        raise TypeError("expected float16 or float32")
+    return out
+
+
+def balance_mask(amax_x, amax_w, alpha: float):
+    """Eq. 3: s = amax_x^alpha / amax_w^(1 - alpha) -> (s fp32 [K], chan_mul = 1/s fp32 [K])."""
+    ax = _arr(amax_x, np.float32)
+    K = ax.shape[0]
+    aw = _arr(amax_w, np.float32, (K,))
+    s = np.empty((K,), np.float32)
+    cm = np.empty((K,), np.float32)
+    _check(_load().oracle_balance_mask(_ptr(ax), _ptr(aw), float(alpha), _ptr(s), _ptr(cm), K), "balance_mask")
+    return s, cm
 
 
 HADAMARD_BLOCK = 128

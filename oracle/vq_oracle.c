@@ -368,6 +368,51 @@ int oracle_dequant(const int32_t* acc, const float* x_scale, const float* w_scal
     return ORACLE_OK;
 }
 
+/* ---- Eq. 3 (Sec. 4.2): the balancing mask from absmax statistics ------------------
+ * s_i = max|X_i|^alpha / max|W_i|^(1 - alpha) for every input channel i, the maxima
+ * taken over the tokens of the calibration activations and over the output channels
+ * of the weight.  Statistics below 1e-5 are raised to 1e-5 and s is kept within
+ * [1e-5, 1e5] (a channel that is all zero must not produce 0 or infinity; the paper
+ * does not treat the case).  chan_mul_i = 1 / s_i in fp32 is what the quantizers take. */
+
+int oracle_channel_absmax_f16(const uint16_t* x_f16, float* amax, int64_t M, int64_t K) {
+    if (!x_f16 || !amax || M < 0 || K <= 0) return ORACLE_ERR_ARG;
+    for (int64_t k = 0; k < K; ++k) amax[k] = 0.0f;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            const float a = fabsf(oracle_half_to_float(x_f16[m * K + k]));
+            if (a > amax[k]) amax[k] = a;
+        }
+    return ORACLE_OK;
+}
+
+int oracle_channel_absmax_f32(const float* w, float* amax, int64_t N, int64_t K) {
+    if (!w || !amax || N < 0 || K <= 0) return ORACLE_ERR_ARG;
+    for (int64_t k = 0; k < K; ++k) amax[k] = 0.0f;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            const float a = fabsf(w[n * K + k]);
+            if (a > amax[k]) amax[k] = a;
+        }
+    return ORACLE_OK;
+}
+
+int oracle_balance_mask(const float* amax_x, const float* amax_w, double alpha, float* s_out,
+                        float* chan_mul_out, int64_t K) {
+    if (!amax_x || !amax_w || !s_out || !chan_mul_out || K <= 0 || !(alpha >= 0.0 && alpha <= 1.0))
+        return ORACLE_ERR_ARG;
+    for (int64_t k = 0; k < K; ++k) {
+        const double ax = amax_x[k] > 1e-5f ? (double)amax_x[k] : 1e-5;
+        const double aw = amax_w[k] > 1e-5f ? (double)amax_w[k] : 1e-5;
+        double s = pow(ax, alpha) / pow(aw, 1.0 - alpha);
+        if (s < 1e-5) s = 1e-5;
+        if (s > 1e5) s = 1e5;
+        s_out[k] = (float)s;
+        chan_mul_out[k] = 1.0f / s_out[k];
+    }
+    return ORACLE_OK;
+}
+
 /* ---- rotation-based balancing (Sec. 4.2), block-diagonal Hadamard matrix ---------- */
 
 static int parity_of(uint64_t v) { /* popcount mod 2 */

@@ -333,3 +333,46 @@ def test_rotation_spreads_an_outlier_channel(oracle):
     assert np.all(np.abs(q).max(axis=1) == 127)
     with pytest.raises(oracle.OracleError):
         oracle.hadamard_rotate(x, None, 96)
+
+
+# ---- Eq. 3: the balancing mask from absmax statistics (Sec. 4.2) ------------------------
+
+def test_channel_absmax_against_numpy(oracle):
+    g = np.random.default_rng(41)
+    x = (g.standard_normal((37, 50)) * g.uniform(0.1, 30, (1, 50))).astype(np.float16)
+    x[:, 7] = 0
+    assert np.array_equal(oracle.channel_absmax(x), np.abs(x.astype(np.float32)).max(axis=0))
+    w = g.standard_normal((19, 50)).astype(np.float32)
+    assert np.array_equal(oracle.channel_absmax(w), np.abs(w).max(axis=0))
+
+
+def test_balance_mask_closed_forms(oracle):
+    ax = np.array([4.0, 9.0, 1.0, 16.0, 0.0, 2.0], np.float32)
+    aw = np.array([1.0, 4.0, 1.0, 0.25, 3.0, 0.0], np.float32)
+    s, cm = oracle.balance_mask(ax, aw, 0.5)
+    # sqrt(ax / aw); all-zero statistics are raised to 1e-5
+    assert np.allclose(s[:4], [2.0, 1.5, 1.0, 8.0], rtol=1e-7)
+    assert np.isclose(s[4], np.sqrt(1e-5 / 3.0), rtol=1e-6) and np.isclose(s[5], np.sqrt(2.0 / 1e-5), rtol=1e-6)
+    assert np.array_equal(cm, (np.float32(1) / s).astype(np.float32))
+    # alpha = 1 moves all of the difficulty to the weights (s = max|X|), alpha = 0 the other way
+    assert np.allclose(oracle.balance_mask(ax[:4], aw[:4], 1.0)[0], ax[:4], rtol=1e-7)
+    assert np.allclose(oracle.balance_mask(ax[:4], aw[:4], 0.0)[0], 1 / aw[:4], rtol=1e-7)
+    with pytest.raises(oracle.OracleError):
+        oracle.balance_mask(ax, aw, 1.5)
+
+
+def test_balance_mask_equalises_the_two_sides_at_half(oracle):
+    # with alpha = 1/2 the scaled activations and the scaled weights get the same per-channel
+    # maximum sqrt(max|X_i| max|W_i|): the difficulty is shared evenly (Sec. 4.2)
+    g = np.random.default_rng(42)
+    x = (g.standard_normal((200, 64)) * np.exp(g.uniform(-2, 3, (1, 64)))).astype(np.float16)
+    w = (g.standard_normal((48, 64)) * 0.05).astype(np.float32)
+    ax, aw = oracle.channel_absmax(x), oracle.channel_absmax(w)
+    s, cm = oracle.balance_mask(ax, aw, 0.5)
+    xa = np.abs(x.astype(np.float64) * cm.astype(np.float64)).max(axis=0)
+    wa = np.abs(w.astype(np.float64) * s.astype(np.float64)).max(axis=0)
+    assert np.allclose(xa, wa, rtol=1e-6) and np.allclose(xa, np.sqrt(ax.astype(np.float64) * aw), rtol=1e-6)
+    # and the product is unchanged (Eq. 3)
+    want = x.astype(np.float64) @ w.astype(np.float64).T
+    got = (x.astype(np.float64) * cm) @ (w.astype(np.float64) * s).T
+    assert np.allclose(got, want, rtol=0, atol=1e-6 * np.abs(want).max())
