@@ -111,6 +111,24 @@ int vq_residual_quantize(const void* x_f16, const void* y_f16, const float* gate
                          void* hip_stream);
 
 /*
+ * Offline calibration of the scaling mask of Sec. 4.2, Eq. 3:
+ *     s_i = max|X_i|^alpha / max|W_i|^(1 - alpha)     for every input channel i.
+ *
+ * vq_channel_absmax: amax[k] = max over the R rows of |a[r,k]| for a dense [R,K] matrix of
+ *                    fp16 (is_f32 = 0: activations of a calibration batch) or fp32
+ *                    (is_f32 = 1: a weight [N,K]).  accumulate = 0 overwrites amax [K];
+ *                    accumulate != 0 combines with the non-negative values already there
+ *                    (the running maximum over several batches or denoising steps).
+ * vq_balance_mask:   s [K] from the two statistics and alpha in [0,1], and chan_mul = 1/s [K],
+ *                    the factor the quantizers take.  Statistics below 1e-5 count as 1e-5 and
+ *                    s is kept within [1e-5, 1e5] (an all-zero channel must not give 0 or inf).
+ *                    The weight side multiplies W[n,k] by s[k] (vq_quantize_weight, chan_s).
+ */
+int vq_channel_absmax(const void* a, int is_f32, float* amax, int R, int K, int accumulate, void* hip_stream);
+int vq_balance_mask(const float* amax_x, const float* amax_w, float alpha, float* s, float* chan_mul, int K,
+                    void* hip_stream);
+
+/*
  * Rotation-based channel balancing, the "dynamic" half of the static-dynamic balancing of
  * Sec. 4.2 (Y = X W^T = (X Q)(W Q)^T for an orthogonal Q; the scaling of Eq. 3 comes first),
  * with the Hadamard transform fused into the quantizer as in Sec. 5.1.  Q is block diagonal

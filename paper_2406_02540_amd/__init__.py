@@ -5,6 +5,8 @@
 """
 from .binding import (  # noqa: F401
     VqError,
+    vq_balance_mask,
+    vq_channel_absmax,
     vq_gelu_quantize,
     vq_gemm_f16,
     vq_hadamard_quantize,

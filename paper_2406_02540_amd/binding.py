@@ -26,6 +26,8 @@ SIGNATURES = {
     "vq_gelu_quantize": (_I, [_P, _I, _P, _P, _P, _I, _I, _P]),
     "vq_layernorm_quantize": (_I, [_P, _P, _P, _I, ctypes.c_float, _P, _P, _P, _I, _I, _P]),
     "vq_residual_quantize": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _I, _I, _P]),
+    "vq_channel_absmax": (_I, [_P, _I, _P, _I, _I, _I, _P]),
+    "vq_balance_mask": (_I, [_P, _P, ctypes.c_float, _P, _P, _I, _P]),
     "vq_hadamard_quantize": (_I, [_P, _P, _P, _P, _I, _I, _P]),
     "vq_rotate_weight": (_I, [_P, _P, _P, _I, _I, _P]),
     "vq_gemm_f16": (_I, [_P, _P, _P, _P, _I, _I, _I, _P]),
@@ -179,6 +181,38 @@ def vq_residual_quantize(x, y, gate=None, tokens_per_sample=None, r=None, chan_m
     _check(lib().vq_residual_quantize(_ptr(x), _ptr(y), _ptr(gate), T, _ptr(r), _ptr(chan_mul), _ptr(xq),
                                       _ptr(x_scale), M, K, _stream(stream)), "vq_residual_quantize")
     return r, xq, x_scale
+
+
+def vq_channel_absmax(a, amax=None, accumulate=False, stream=None):
+    """Per-column absmax of fp16 activations [M,K] or fp32 weights [N,K] -> amax fp32 [K]."""
+    if not isinstance(a, torch.Tensor) or a.dtype not in (torch.float16, torch.float32):
+        raise TypeError("a: expected a float16 or float32 device tensor")
+    a = _dev(a, a.dtype, "a")
+    R, K = a.shape
+    if amax is None:
+        if accumulate:
+            raise ValueError("accumulate needs the running amax")
+        amax = torch.empty((K,), dtype=torch.float32, device=a.device)
+    _dev(amax, torch.float32, "amax")
+    if tuple(amax.shape) != (K,):
+        raise ValueError("amax must have shape [K]")
+    _check(lib().vq_channel_absmax(_ptr(a), int(a.dtype == torch.float32), _ptr(amax), R, K, int(bool(accumulate)),
+                                   _stream(stream)), "vq_channel_absmax")
+    return amax
+
+
+def vq_balance_mask(amax_x, amax_w, alpha, stream=None):
+    """Eq. 3: (s, chan_mul = 1/s), fp32 [K] each, from the two absmax statistics."""
+    amax_x = _dev(amax_x, torch.float32, "amax_x")
+    amax_w = _dev(amax_w, torch.float32, "amax_w")
+    K = amax_x.shape[0]
+    if tuple(amax_x.shape) != (K,) or tuple(amax_w.shape) != (K,):
+        raise ValueError("statistics must have shape [K]")
+    s = torch.empty((K,), dtype=torch.float32, device=amax_x.device)
+    cm = torch.empty_like(s)
+    _check(lib().vq_balance_mask(_ptr(amax_x), _ptr(amax_w), float(alpha), _ptr(s), _ptr(cm), K, _stream(stream)),
+           "vq_balance_mask")
+    return s, cm
 
 
 def vq_hadamard_quantize(x, chan_mul=None, xq=None, x_scale=None, stream=None):

@@ -176,6 +176,26 @@ int vq_residual_quantize(const void* x_f16, const void* y_f16, const float* gate
                                                       xq, x_scale, M, K, (hipStream_t)hip_stream));
 }
 
+int vq_channel_absmax(const void* a, int is_f32, float* amax, int R, int K, int accumulate, void* hip_stream) {
+    if (R < 0 || K <= 0 || K > VQ_MAX_K || (is_f32 != 0 && is_f32 != 1)) return VQ_ERR_SHAPE;
+    if (!amax || (R > 0 && !a)) return VQ_ERR_NULL;
+    if (misaligned(amax) || (a && misaligned(a))) return VQ_ERR_ALIGN;
+    if (R == 0 && accumulate) return VQ_OK;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_channel_absmax(a, is_f32, amax, R, K, accumulate, (hipStream_t)hip_stream));
+}
+
+int vq_balance_mask(const float* amax_x, const float* amax_w, float alpha, float* s, float* chan_mul, int K,
+                    void* hip_stream) {
+    if (K <= 0 || K > VQ_MAX_K || !(alpha >= 0.0f && alpha <= 1.0f)) return VQ_ERR_SHAPE;
+    if (!amax_x || !amax_w || !s || !chan_mul) return VQ_ERR_NULL;
+    if (misaligned(amax_x) || misaligned(amax_w) || misaligned(s) || misaligned(chan_mul)) return VQ_ERR_ALIGN;
+    const int arch = check_arch();
+    if (arch != VQ_OK) return arch;
+    return launch_status(vq::launch_balance_mask(amax_x, amax_w, alpha, s, chan_mul, K, (hipStream_t)hip_stream));
+}
+
 int vq_gemm_f16(const void* x_f16, const void* w_f16, const void* bias_f16, void* y_f16, int M, int N, int K,
                 void* hip_stream) {
     if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K || K % 8 != 0) return VQ_ERR_SHAPE;

@@ -24,6 +24,12 @@ hipError_t launch_residual_quantize(const void* x_f16, const void* y_f16, const 
                                     int tokens_per_sample, void* r_f16, const float* chan_mul, int8_t* xq,
                                     float* x_scale, int M, int K, hipStream_t stream);
 
+// Calibration of Eq. 3's mask: column absmax of fp16 (is_f32 = 0) or fp32 rows, and the mask itself.
+hipError_t launch_channel_absmax(const void* a, int is_f32, float* amax, int R, int K, int accumulate,
+                                 hipStream_t stream);
+hipError_t launch_balance_mask(const float* amax_x, const float* amax_w, float alpha, float* s, float* chan_mul,
+                               int K, hipStream_t stream);
+
 hipError_t launch_quantize_static(const void* x_f16, const float* chan_mul, float inv_scale, int8_t* xq,
                                   int M, int K, hipStream_t stream);
 

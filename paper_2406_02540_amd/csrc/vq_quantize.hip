@@ -112,6 +112,44 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_static_elems(
     }
 }
 
+// Calibration side of Eq. 3 (Sec. 4.2): per-input-channel absmax over the rows of a matrix
+// (tokens of a calibration batch, or output channels of a weight).  Thread t of a block owns
+// column 256 b_x + t for a slab of rows; slabs are combined with an integer atomic max on
+// the bit pattern (non-negative floats order like their bits).  amax must hold valid
+// non-negative values on entry (zeros, or the running maximum of earlier batches).
+template <typename T>
+__global__ __launch_bounds__(kQuantThreads) void channel_absmax_cols(const T* __restrict__ a,
+                                                                     float* __restrict__ amax, int R, int K,
+                                                                     int rows_per_block) {
+    const int k = blockIdx.x * kQuantThreads + threadIdx.x;
+    if (k >= K) return;
+    const long r0 = (long)blockIdx.y * rows_per_block;
+    const long r1 = r0 + rows_per_block < R ? r0 + rows_per_block : R;
+    float m = 0.0f;
+    for (long r = r0; r < r1; ++r) m = fmaxf(m, fabsf((float)a[r * K + k]));
+    atomicMax((int*)amax + k, __builtin_bit_cast(int, m));
+}
+
+__global__ __launch_bounds__(kQuantThreads) void fill_zero_f32(float* __restrict__ p, int n) {
+    const int i = blockIdx.x * kQuantThreads + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// s = max|X|^alpha / max|W|^(1 - alpha) per channel, statistics raised to 1e-5, s kept in
+// [1e-5, 1e5]; chan_mul = 1 / s (IEEE division).
+__global__ __launch_bounds__(kQuantThreads) void balance_mask_elems(const float* __restrict__ ax,
+                                                                    const float* __restrict__ aw, float alpha,
+                                                                    float* __restrict__ s_out,
+                                                                    float* __restrict__ chan_mul, int K) {
+    const int k = blockIdx.x * kQuantThreads + threadIdx.x;
+    if (k >= K) return;
+    const float x = fmaxf(ax[k], 1e-5f), w = fmaxf(aw[k], 1e-5f);
+    float s = powf(x, alpha) / powf(w, 1.0f - alpha);
+    s = fminf(fmaxf(s, 1e-5f), 1e5f);
+    s_out[k] = s;
+    chan_mul[k] = 1.0f / s;
+}
+
 // Offline weight quantizer: one workgroup per output channel, fp32 input.
 // BITS == 4 writes two nibbles per byte (k even in bits 0..3, k odd in 4..7).
 template <int BITS, bool HAS_S>
@@ -207,6 +245,38 @@ hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, i
     else
         hipLaunchKernelGGL((quantize_tokens_generic<false>), grid, block, 0, stream,
                            (const _Float16*)x_f16, (const float*)nullptr, xq, x_scale, K);
+    return hipGetLastError();
+}
+
+hipError_t launch_channel_absmax(const void* a, int is_f32, float* amax, int R, int K, int accumulate,
+                                 hipStream_t stream) {
+    const dim3 block(kQuantThreads);
+    if (!accumulate) {
+        hipLaunchKernelGGL(fill_zero_f32, dim3((unsigned)((K + kQuantThreads - 1) / kQuantThreads)), block, 0,
+                           stream, amax, K);
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    }
+    if (R == 0) return hipSuccess;
+    const int col_blocks = (K + kQuantThreads - 1) / kQuantThreads;
+    // enough row slabs to fill the chip, at least 64 rows each
+    int slabs = (2048 + col_blocks - 1) / col_blocks;
+    if (slabs > (R + 63) / 64) slabs = (R + 63) / 64;
+    if (slabs < 1) slabs = 1;
+    const int rows_per_block = (R + slabs - 1) / slabs;
+    const dim3 grid((unsigned)col_blocks, (unsigned)((R + rows_per_block - 1) / rows_per_block));
+    if (is_f32)
+        hipLaunchKernelGGL((channel_absmax_cols<float>), grid, block, 0, stream, (const float*)a, amax, R, K,
+                           rows_per_block);
+    else
+        hipLaunchKernelGGL((channel_absmax_cols<_Float16>), grid, block, 0, stream, (const _Float16*)a, amax, R,
+                           K, rows_per_block);
+    return hipGetLastError();
+}
+
+hipError_t launch_balance_mask(const float* amax_x, const float* amax_w, float alpha, float* s, float* chan_mul,
+                               int K, hipStream_t stream) {
+    hipLaunchKernelGGL(balance_mask_elems, dim3((unsigned)((K + kQuantThreads - 1) / kQuantThreads)),
+                       dim3(kQuantThreads), 0, stream, amax_x, amax_w, alpha, s, chan_mul, K);
     return hipGetLastError();
 }
 

@@ -136,3 +136,60 @@ def test_comparison_calls_rejected_or_empty(vq):
     empty = torch.zeros((0, 64), dtype=torch.float16, device="cuda")
     assert vq.vq_quantize_static(empty, 1.0).shape == (0, 64)
     assert vq.vq_gemm_f16(empty, torch.zeros((8, 64), dtype=torch.float16, device="cuda")).shape == (0, 8)
+
+
+# ---- offline calibration of Eq. 3's mask (Sec. 4.2) -------------------------------------------
+
+@pytest.mark.parametrize("R,K", [(1, 1), (37, 50), (300, 1152), (5000, 333), (240, 4096), (4099, 1160)])
+def test_channel_absmax_bit_exact(vq, oracle, R, K):
+    say(f"channel_absmax R={R} K={K}")
+    g = np.random.default_rng(700 + R + K)
+    x = (g.standard_normal((R, K)) * np.exp(g.uniform(-2, 3, (1, K)))).astype(np.float16)
+    if K > 3:
+        x[:, 3] = 0
+    got = vq.vq_channel_absmax(dev(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(got), oracle.channel_absmax(x))
+    w = g.standard_normal((R, K)).astype(np.float32)
+    assert np.array_equal(host(vq.vq_channel_absmax(dev(w))), oracle.channel_absmax(w))
+    # the running maximum over two batches is the maximum over both
+    x2 = (g.standard_normal((max(1, R // 2), K)) * 40).astype(np.float16)
+    vq.vq_channel_absmax(dev(x2), got, accumulate=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(got), oracle.channel_absmax(np.concatenate([x, x2])))
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.3, 0.5, 1.0])
+def test_balance_mask(vq, oracle, alpha):
+    g = np.random.default_rng(800)
+    K = 1152
+    ax = np.exp(g.uniform(-3, 5, K)).astype(np.float32)
+    aw = np.exp(g.uniform(-6, 0, K)).astype(np.float32)
+    ax[5] = 0; aw[9] = 0; ax[11] = 0; aw[11] = 0
+    s_ref, cm_ref = oracle.balance_mask(ax, aw, alpha)
+    s, cm = vq.vq_balance_mask(dev(ax), dev(aw), alpha)
+    torch.cuda.synchronize()
+    s, cm = host(s), host(cm)
+    # powf against the oracle's fp64 pow: a few fp32 ulps; the reciprocal is the exact IEEE one
+    assert np.allclose(s, s_ref, rtol=2e-6, atol=0) and np.all((s >= 1e-5) & (s <= 1e5))
+    assert np.array_equal(cm, (np.float32(1) / s).astype(np.float32))
+
+
+def test_calibrated_layer_end_to_end(vq, oracle):
+    """Statistics, mask, weight quantizer, activation quantizer and GEMM, all on the device, against the
+    oracle's pipeline fed with the device's mask (the mask itself is compared above)."""
+    from parity_util import assert_fp16_close
+    g = np.random.default_rng(801)
+    M, N, K = 520, 264, 1152
+    x = (g.standard_normal((M, K)) * np.exp(g.uniform(-2, 2, (1, K)))).astype(np.float16)
+    w = (g.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (g.standard_normal(N) * 0.01).astype(np.float16)
+    xd, wd = dev(x), dev(w)
+    s, cm = vq.vq_balance_mask(vq.vq_channel_absmax(xd), vq.vq_channel_absmax(wd), 0.5)
+    wq, ws = vq.vq_quantize_weight(wd, s, 8)
+    y = vq.vq_linear(xd, cm, wq, 8, ws, dev(b))
+    torch.cuda.synchronize()
+    wq_ref, ws_ref = oracle.quantize_weight(w, host(s), 8)
+    ref = oracle.linear(x, host(cm), wq_ref, 8, ws_ref, b)
+    assert np.array_equal(host(wq), wq_ref) and np.array_equal(host(ws), ws_ref)
+    assert_fp16_close(host(y), ref["y"], ref["acc"], ref["x_scale"], ws_ref, b)

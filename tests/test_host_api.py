@@ -128,6 +128,16 @@ def test_rotation_and_comparison_argument_errors(lib):
     assert qs(P(A), None, F(-1.0), P(A), 4, 64, None) == 2
     assert qs(P(A), None, F(0.5), None, 4, 64, None) == 1
     assert qs(P(A), None, F(0.5), P(A), 4, 64, None) == 6
+    ca, bm = lib.vq_channel_absmax, lib.vq_balance_mask
+    assert ca(P(A), 2, P(A), 4, 64, 0, None) == 2
+    assert ca(P(A), 0, None, 4, 64, 0, None) == 1
+    assert ca(None, 0, P(A), 4, 64, 0, None) == 1
+    assert ca(P(A + 2), 0, P(A), 4, 64, 0, None) == 3
+    assert ca(None, 0, P(A), 0, 64, 1, None) == 0
+    assert ca(P(A), 1, P(A), 4, 64, 0, None) == 6
+    assert bm(P(A), P(A), F(1.5), P(A), P(A), 64, None) == 2
+    assert bm(P(A), None, F(0.5), P(A), P(A), 64, None) == 1
+    assert bm(P(A), P(A), F(0.5), P(A), P(A), 64, None) == 6
 
 
 def test_gemm_argument_errors(lib):
