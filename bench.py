@@ -35,7 +35,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=3)
-    p.add_argument("--workload", default="video", choices=["video", "image", "video-w4"])
+    p.add_argument("--workload", default="video", choices=["video", "image", "video-w4", "sweep"])
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-seconds", type=float, default=15.0,
                    help="about how long the CPU oracle leg may run (it picks its token sample to fit)")
@@ -59,6 +59,95 @@ def layer_specs(workload):
             s.w_bits = 4
         return specs, "video-DiT linears, 32768 tokens, hidden 1152, W4A8 (configs[3] shapes, 4-bit weights)"
     return specs, "video-DiT linears, 32768 tokens (+240 text tokens), hidden 1152, W8A8 (configs[3])"
+
+
+def run_sweep(args, vq, wl, ceilings):
+    """configs[4]: every linear of a 28-block video DiT (168 layers, about 30 % of them W4A8 by a seeded plan),
+    one step = one denoising step through all of them; the activations of step t are the base activations
+    times 0.5 + t/20, materialised before the timed region."""
+    import numpy as np
+    import torch
+    specs = wl.config5()
+    t0 = time.time()
+    layers = []
+    for s in specs:
+        w, bias, sm, cm = wl.draw_weights(s)
+        wq, ws = vq.vq_quantize_weight(torch.from_numpy(w).cuda(), None if sm is None else torch.from_numpy(sm).cuda(),
+                                       s.w_bits)
+        layers.append(dict(spec=s, wq=wq, ws=ws, bias=torch.from_numpy(bias).cuda(),
+                           cm=None if cm is None else torch.from_numpy(cm).cuda()))
+    # one base activation per input shape, as in the sampled parity test of this configuration
+    base, y, work = {}, {}, {}
+    for s in specs:
+        if (s.M, s.K) not in base:
+            base[(s.M, s.K)] = torch.from_numpy(wl.draw_x(s)).cuda()
+        if (s.M, s.N) not in y:
+            y[(s.M, s.N)] = torch.empty((s.M, s.N), dtype=torch.float16, device="cuda")
+        key = (s.M, s.N, s.K)
+        if key not in work:
+            work[key] = torch.empty((vq.vq_linear_workspace_bytes(s.M, s.N, s.K, 8),), dtype=torch.uint8, device="cuda")
+    n_t = 20
+    xs = {t: {k: (v.float() * wl.config5_step_scale(t)).half() for k, v in base.items()} for t in range(1, n_t + 1)}
+    torch.cuda.synchronize()
+    log(f"sweep: {len(layers)} layers quantized, activations of {n_t} steps materialised in {time.time() - t0:.1f} s")
+
+    def step(t):
+        x = xs[t]
+        for L in layers:
+            s = L["spec"]
+            vq.vq_linear(x[(s.M, s.K)], L["cm"], L["wq"], s.w_bits, L["ws"], L["bias"], y=y[(s.M, s.N)],
+                         workspace=work[(s.M, s.N, s.K)])
+
+    for i in range(args.warmup):
+        step(1 + i % n_t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(1 + i % n_t)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ops = sum(L["spec"].ops for L in layers)
+    tops = ops / (ms * 1e-3) / 1e12
+    # GEMM launches alone, one step, HIP events between the two kernels of every layer
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in layers]
+    xq = {k: torch.empty((k[0], k[1]), dtype=torch.int8, device="cuda") for k in base}
+    xsc = {k: torch.empty((k[0],), dtype=torch.float32, device="cuda") for k in base}
+    for (e0, e1, e2), L in zip(ev, layers):
+        s = L["spec"]
+        k = (s.M, s.K)
+        e0.record()
+        vq.vq_quantize_per_token(xs[10][k], L["cm"], xq=xq[k], x_scale=xsc[k])
+        e1.record()
+        (vq.vq_gemm_w8a8 if s.w_bits == 8 else vq.vq_gemm_w4a8)(xq[k], xsc[k], L["wq"], L["ws"], L["bias"], y=y[(s.M, s.N)])
+        e2.record()
+    torch.cuda.synchronize()
+    big = [(L, e) for L, e in zip(layers, ev) if L["spec"].M >= 1024]
+    g_ops = sum(L["spec"].ops for L, _ in big)
+    g_time = sum(e[1].elapsed_time(e[2]) for _, e in big) * 1e-3
+    q_bytes = sum(quant_bytes(L["spec"], L["cm"] is not None) for L, _ in big)
+    q_time = sum(e[0].elapsed_time(e[1]) for _, e in big) * 1e-3
+    g_ach, q_ach = g_ops / g_time / 1e12, q_bytes / q_time / 1e9
+    n4 = sum(1 for L in layers if L["spec"].w_bits == 4)
+    out = {
+        "metric": "quantized-linear int8 TOPS (quant+GEMM+dequant)", "value": round(tops, 2), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "full-step sweep: all 168 linears of a 28-block video DiT at 32768 tokens, seeded mixed "
+                               "precision (%d W4A8, %d W8A8), activations scaled per denoising step (configs[4])"
+                               % (n4, len(layers) - n4),
+                   "ops_per_step": ops},
+        "frac_of_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
+        "roofline": dict(kernel="gemm_i8_dequant", bound="mfma", achieved=round(g_ach, 1), peak=round(INT8_MFMA_PEAK_TOPS, 1),
+                         unit="TOP/s", frac=round(g_ach / INT8_MFMA_PEAK_TOPS, 4), traffic=None,
+                         launches="the %d GEMM launches with M >= 1024 of one step, HIP-event durations" % len(big)),
+        "roofline_quantizer": dict(kernel="quantize_tokens_wave", bound="hbm", achieved=round(q_ach, 1), peak=HBM_PEAK_GBS,
+                                   unit="GB/s", frac=round(q_ach / HBM_PEAK_GBS, 4), traffic=None),
+        "cpu_baseline": None,
+        "measured_ceilings": ceilings,
+    }
+    log(f"sweep: {ms:.2f} ms per denoising step, {tops:.0f} TOPS; GEMM launches {g_ach:.0f} TOP/s, quantizer {q_ach:.0f} GB/s")
+    print(json.dumps(out), flush=True)
 
 
 def gemm_bytes(s):
@@ -102,6 +191,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}))
+        return
+    if args.workload == "sweep":
+        run_sweep(args, vq, wl, ceilings)
         return
     specs, workload_name = layer_specs(args.workload)
 
