@@ -56,7 +56,8 @@ __global__ void copy16(const v4i* __restrict__ in, v4i* __restrict__ out, size_t
 }
 
 static float gauss() {
-    const float u = (rand() + 1.0f) / (RAND_MAX + 2.0f), v = (rand() + 1.0f) / (RAND_MAX + 2.0f);
+    const double span = (double)RAND_MAX + 2.0;
+    const float u = (float)((rand() + 1.0) / span), v = (float)((rand() + 1.0) / span);
     return sqrtf(-2.0f * logf(u)) * cosf(6.2831853f * v);
 }
 static int8_t clamp8(float g) { return (int8_t)fmaxf(-127.0f, fminf(127.0f, roundf(g))); }
