@@ -226,6 +226,10 @@ def test_rotate_weight_and_rotated_layer(vq, oracle):
     torch.cuda.synchronize()
     norm = np.sqrt((w_rot_ref.astype(np.float64) ** 2).reshape(N, K // 128, 128).sum(axis=2)).repeat(128, axis=1)
     assert np.all(np.abs(host(w_rot).astype(np.float64) - w_rot_ref) <= 1e-6 * norm + 1e-12)
+    w_in_place = dev(w)
+    vq.vq_rotate_weight(w_in_place, dev(s), out=w_in_place)  # input and output may be one buffer
+    torch.cuda.synchronize()
+    assert np.array_equal(host(w_in_place), host(w_rot))
     # the whole rotated W8A8 layer on the GPU ...
     wq, ws = vq.vq_quantize_weight(w_rot, None, 8)
     xq, xs = vq.vq_hadamard_quantize(dev(x), dev(cm))

@@ -3,7 +3,9 @@ the operations the quantizer is fused into, Sec. 5.1 "Hardware Implementation
 Settings") to things other than themselves: library routines that compute the same
 textbook function by another route (scipy's normal distribution function, torch's
 float64 gelu and layer_norm, numpy's float32/float16 arithmetic), closed forms,
-symmetries and hand-worked roundings.
+symmetries and hand-worked roundings.  Further down, in the same way: the block Hadamard
+rotation (Sec. 4.2), the mask of Eq. 3 from absmax statistics, and the two comparison points of
+Sec. 5.3 (FP16 layer, static quantizer).
 """
 import numpy as np
 import pytest
