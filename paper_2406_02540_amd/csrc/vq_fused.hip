@@ -278,10 +278,11 @@ hipError_t launch_fused_nch(int nch, const FusedArgs& a, hipStream_t stream) {
 template <int PRODUCER>
 hipError_t launch_producer(const FusedArgs& a, hipStream_t stream) {
     const int k8 = a.K8;
-    // 16 lanes per token when that divides a short row exactly (K = 1152: 16 lanes x 9
-    // chunks keep every lane busy), a whole wavefront per token otherwise
-    if (k8 % 64 != 0 && k8 % 16 == 0 && k8 / 16 <= 16) return launch_fused_nch<PRODUCER, 16>(k8 / 16, a, stream);
-    return launch_fused_nch<PRODUCER, 64>((k8 + 63) / 64, a, stream);
+    switch (lanes_for_row(k8)) {
+        case 16: return launch_fused_nch<PRODUCER, 16>((k8 + 15) / 16, a, stream);
+        case 32: return launch_fused_nch<PRODUCER, 32>((k8 + 31) / 32, a, stream);
+        default: return launch_fused_nch<PRODUCER, 64>((k8 + 63) / 64, a, stream);
+    }
 }
 
 }  // namespace

@@ -25,15 +25,71 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // The token row held in registers (layout and steps: vq_quantize_row.h).  LANES is chosen
 // so that K / 8 = NCH * LANES exactly where possible (K = 1152: 16 lanes x 9 chunks),
-// which keeps every lane busy on every instruction.
-template <int NCH, int LANES, bool HAS_MUL>
-__global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave(
+// which keeps every lane busy on every instruction.  This instantiation folds the
+// balancing factor in as the row arrives and keeps the products in fp32.
+template <int NCH, int LANES>
+__global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave_mul(
     const half8* __restrict__ x, const float4v* __restrict__ chan_mul, int2v* __restrict__ xq,
     float* __restrict__ x_scale, int M, int K8) {
     const RowLane<LANES> rl(M);
     float t[NCH][8];
-    load_row<NCH, LANES, HAS_MUL>(x + (rl.row_ok ? rl.m : 0) * K8, rl.row_ok, rl.sub, K8, t, chan_mul);
+    load_row<NCH, LANES, true>(x + (rl.row_ok ? rl.m : 0) * K8, rl.row_ok, rl.sub, K8, t, chan_mul);
     fold_quantize_store<NCH, LANES, false>(t, nullptr, rl.row_ok, rl.sub, K8, rl.m, xq, x_scale);
+}
+
+// Wavefronts per SIMD the register allocation below is held to (4 registers per chunk of the row,
+// 512 registers per SIMD lane).
+constexpr int quant_waves(int nch) { return nch <= 10 ? 8 : nch == 11 ? 7 : nch == 12 ? 6 : nch <= 15 ? 5 : 4; }
+
+// No balancing factor: the row stays in registers as the fp16 it arrived as (half the
+// registers of an fp32 copy, so that twice as many wavefronts are resident and every
+// workgroup of the video-sized problem is in flight at once).  The absolute maximum is
+// taken on the fp16 values (exact: fp16 -> fp32 is monotonic and exact), each value is
+// widened once more where it is scaled and rounded.
+template <int NCH, int LANES>
+__global__ __launch_bounds__(kQuantThreads, quant_waves(NCH)) void quantize_tokens_wave(
+    const half8* __restrict__ x, int2v* __restrict__ xq, float* __restrict__ x_scale, int M, int K8) {
+    const RowLane<LANES> rl(M);
+    const half8* row = x + (rl.row_ok ? rl.m : 0) * K8;
+    half8 raw[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = i * LANES + rl.sub;
+        if (rl.row_ok && c < K8) raw[i] = __builtin_nontemporal_load(row + c);
+        else raw[i] = (half8){0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    half8 hmax = __builtin_elementwise_abs(raw[0]);
+#pragma unroll
+    for (int i = 1; i < NCH; ++i) hmax = __builtin_elementwise_max(hmax, __builtin_elementwise_abs(raw[i]));
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, (float)hmax[j]);
+    amax = group_max<LANES>(amax);
+
+    float scale = 0.0f, inv = 0.0f;
+    if (amax != 0.0f) {
+        scale = amax / 127.0f;
+        inv = 127.0f / amax;
+    }
+    if (rl.row_ok && rl.sub == 0) x_scale[rl.m] = scale;
+
+    int2v* qrow = xq + (rl.row_ok ? rl.m : 0) * K8;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = i * LANES + rl.sub;
+        if (rl.row_ok && c < K8) {
+            // (opaque to the optimizer: the widening happens here, chunk by chunk, and no
+            // fp32 copy of the row is carried over from above)
+            asm volatile("" : "+v"(raw[i]));
+            int q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = quantize_one((float)raw[i][j], inv, 127.0f);
+            int2v o;
+            o.x = pack4(q[0], q[1], q[2], q[3]);
+            o.y = pack4(q[4], q[5], q[6], q[7]);
+            qrow[c] = o;
+        }
+    }
 }
 
 __device__ __forceinline__ float block_max(float v, float* red) {
@@ -79,36 +135,64 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_tokens_generic(
     }
 }
 
-// Static quantizer (the comparison point: one scale for the whole tensor, fixed beforehand):
-// element-wise, 8 values per thread where the rows are whole 16-byte chunks.
-template <bool VEC>
+// Static quantizer (the comparison point: one scale for the whole tensor, fixed beforehand).
+// Rows of whole 16-byte chunks: a wavefront takes CHUNKS KiB of contiguous input, a thread
+// its chunks one wavefront width apart (every load and store instruction of a wavefront is
+// contiguous), all loads first.
+template <bool HAS_MUL, int CHUNKS>
+__global__ __launch_bounds__(kQuantThreads, 8) void quantize_static_chunks(
+    const half8* __restrict__ x, const float4v* __restrict__ chan_mul, float inv, int2v* __restrict__ xq,
+    unsigned chunks, unsigned K8) {
+    const unsigned base = blockIdx.x * (kQuantThreads * CHUNKS) + (threadIdx.x >> 6) * (kWave * CHUNKS) +
+                          (threadIdx.x & (kWave - 1));
+    half8 v[CHUNKS];
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        const unsigned c = base + i * kWave;
+        if (c < chunks) v[i] = __builtin_nontemporal_load(x + c);
+    }
+    int2v o[CHUNKS];
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        const unsigned c = base + i * kWave;
+        if (c < chunks) {
+            float t[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[j] = (float)v[i][j];
+            if (HAS_MUL) {
+                const unsigned k8 = c % K8;
+                const float4v m0 = chan_mul[2 * k8], m1 = chan_mul[2 * k8 + 1];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    t[j] = t[j] * m0[j];
+                    t[4 + j] = t[4 + j] * m1[j];
+                }
+            }
+            int q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = quantize_one(t[j], inv, 127.0f);
+            o[i].x = pack4(q[0], q[1], q[2], q[3]);
+            o[i].y = pack4(q[4], q[5], q[6], q[7]);
+        }
+    }
+    // the stores leave together, behind the last load (reads and writes in bursts, not mixed)
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        const unsigned c = base + i * kWave;
+        if (c < chunks) xq[c] = o[i];
+    }
+}
+
+// Any K: element by element.
 __global__ __launch_bounds__(kQuantThreads) void quantize_static_elems(
     const _Float16* __restrict__ x, const float* __restrict__ chan_mul, float inv, int8_t* __restrict__ xq,
     long total, int K) {
     const long step = (long)gridDim.x * kQuantThreads;
-    if (VEC) {
-        const int K8 = K / 8;
-        for (long c = (long)blockIdx.x * kQuantThreads + threadIdx.x; c < total / 8; c += step) {
-            const half8 v = __builtin_nontemporal_load((const half8*)x + c);
-            const int k = (int)(c % K8) * 8;
-            int q[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                float t = (float)v[j];
-                if (chan_mul) t = t * chan_mul[k + j];
-                q[j] = quantize_one(t, inv, 127.0f);
-            }
-            int2v o;
-            o.x = pack4(q[0], q[1], q[2], q[3]);
-            o.y = pack4(q[4], q[5], q[6], q[7]);
-            ((int2v*)xq)[c] = o;
-        }
-    } else {
-        for (long e = (long)blockIdx.x * kQuantThreads + threadIdx.x; e < total; e += step) {
-            float t = (float)x[e];
-            if (chan_mul) t = t * chan_mul[e % K];
-            xq[e] = (int8_t)quantize_one(t, inv, 127.0f);
-        }
+    for (long e = (long)blockIdx.x * kQuantThreads + threadIdx.x; e < total; e += step) {
+        float t = (float)x[e];
+        if (chan_mul) t = t * chan_mul[e % K];
+        xq[e] = (int8_t)quantize_one(t, inv, 127.0f);
     }
 }
 
@@ -200,11 +284,11 @@ hipError_t launch_wave(const void* x, const float* chan_mul, int8_t* xq, float* 
     constexpr int rows_per_block = kRowsPerBlock * (kWave / LANES);
     const dim3 grid((unsigned)((M + rows_per_block - 1) / rows_per_block)), block(kQuantThreads);
     if (chan_mul)
-        hipLaunchKernelGGL((quantize_tokens_wave<NCH, LANES, true>), grid, block, 0, stream,
+        hipLaunchKernelGGL((quantize_tokens_wave_mul<NCH, LANES>), grid, block, 0, stream,
                            (const half8*)x, (const float4v*)chan_mul, (int2v*)xq, x_scale, M, K / 8);
     else
-        hipLaunchKernelGGL((quantize_tokens_wave<NCH, LANES, false>), grid, block, 0, stream,
-                           (const half8*)x, (const float4v*)nullptr, (int2v*)xq, x_scale, M, K / 8);
+        hipLaunchKernelGGL((quantize_tokens_wave<NCH, LANES>), grid, block, 0, stream,
+                           (const half8*)x, (int2v*)xq, x_scale, M, K / 8);
     return hipGetLastError();
 }
 
@@ -230,7 +314,14 @@ hipError_t launch_quantize_per_token(const void* x_f16, const float* chan_mul, i
                      (chan_mul == nullptr || (uintptr_t)chan_mul % 16 == 0);
     if (vec) {
         const int k8 = K / 8;
-        // the widest lane group that divides the row exactly; a whole wavefront otherwise
+        if (chan_mul) {  // the row is held as fp32 products: few chunks per lane first
+            switch (lanes_for_row(k8)) {
+                case 16: return launch_wave_nch<16>((k8 + 15) / 16, x_f16, chan_mul, xq, x_scale, M, K, stream);
+                case 32: return launch_wave_nch<32>((k8 + 31) / 32, x_f16, chan_mul, xq, x_scale, M, K, stream);
+                default: return launch_wave_nch<64>((k8 + 63) / 64, x_f16, chan_mul, xq, x_scale, M, K, stream);
+            }
+        }
+        // held as fp16: the widest lane group that divides the row exactly; a whole wavefront otherwise
         if (k8 % 64 == 0) return launch_wave_nch<64>(k8 / 64, x_f16, chan_mul, xq, x_scale, M, K, stream);
         if (k8 % 32 == 0 && k8 / 32 <= 16)
             return launch_wave_nch<32>(k8 / 32, x_f16, chan_mul, xq, x_scale, M, K, stream);
@@ -280,19 +371,47 @@ hipError_t launch_balance_mask(const float* amax_x, const float* amax_w, float a
     return hipGetLastError();
 }
 
+template <int CHUNKS>
+hipError_t launch_static_chunks(const void* x_f16, const float* chan_mul, float inv_scale, int8_t* xq,
+                                unsigned chunks, unsigned K8, hipStream_t stream) {
+    constexpr unsigned per_block = kQuantThreads * CHUNKS;
+    const dim3 grid((chunks + per_block - 1) / per_block), block(kQuantThreads);
+    if (chan_mul)
+        hipLaunchKernelGGL((quantize_static_chunks<true, CHUNKS>), grid, block, 0, stream, (const half8*)x_f16,
+                           (const float4v*)chan_mul, inv_scale, (int2v*)xq, chunks, K8);
+    else
+        hipLaunchKernelGGL((quantize_static_chunks<false, CHUNKS>), grid, block, 0, stream, (const half8*)x_f16,
+                           (const float4v*)nullptr, inv_scale, (int2v*)xq, chunks, K8);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_static(const void* x_f16, const float* chan_mul, float inv_scale, int8_t* xq,
                                   int M, int K, hipStream_t stream) {
     const long total = (long)M * K;
-    const bool vec = (K % 8 == 0);
-    const long work = vec ? total / 8 : total;
-    const long blocks = (work + kQuantThreads - 1) / kQuantThreads;
+    if (K % 8 == 0 && total / 8 < (1L << 31)) {
+        // Chunks per thread: the count whose grid wastes least of its last round of resident
+        // workgroups (8 per compute unit, 256 units).
+        const long chunks = total / 8, slots = 8 * 256;
+        int best = 8;
+        long best_cost = 1L << 62;
+        for (int u : {8, 9, 10}) {
+            const long blocks = (chunks + kQuantThreads * u - 1) / (kQuantThreads * u);
+            const long cost = (blocks + slots - 1) / slots * u;
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = u;
+            }
+        }
+        switch (best) {
+            case 9: return launch_static_chunks<9>(x_f16, chan_mul, inv_scale, xq, (unsigned)chunks, (unsigned)(K / 8), stream);
+            case 10: return launch_static_chunks<10>(x_f16, chan_mul, inv_scale, xq, (unsigned)chunks, (unsigned)(K / 8), stream);
+            default: return launch_static_chunks<8>(x_f16, chan_mul, inv_scale, xq, (unsigned)chunks, (unsigned)(K / 8), stream);
+        }
+    }
+    const long blocks = (total + kQuantThreads - 1) / kQuantThreads;
     const dim3 grid((unsigned)(blocks < 16384 ? (blocks < 1 ? 1 : blocks) : 16384)), block(kQuantThreads);
-    if (vec)
-        hipLaunchKernelGGL((quantize_static_elems<true>), grid, block, 0, stream, (const _Float16*)x_f16,
-                           chan_mul, inv_scale, xq, total, K);
-    else
-        hipLaunchKernelGGL((quantize_static_elems<false>), grid, block, 0, stream, (const _Float16*)x_f16,
-                           chan_mul, inv_scale, xq, total, K);
+    hipLaunchKernelGGL(quantize_static_elems, grid, block, 0, stream, (const _Float16*)x_f16, chan_mul, inv_scale,
+                       xq, total, K);
     return hipGetLastError();
 }
 
