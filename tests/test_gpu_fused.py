@@ -80,7 +80,7 @@ def rows(seed, M, K, spread=True):
 
 
 FUSED_SHAPES = [(1, 8), (5, 64), (37, 1152), (130, 4608), (7, 4096), (3, 8192), (9, 2048), (6, 520),
-                (3, 3584), (1000, 1152), (2, 5000)]
+                (3, 3584), (1000, 1152), (2, 5000), (11, 384), (11, 1280), (11, 2304)]
 
 
 @pytest.mark.parametrize("M,K", FUSED_SHAPES)
@@ -192,7 +192,8 @@ def test_full_size_layernorm_feeds_qkv_and_residual_feeds_it(vq, oracle):
 
 # ---- rotation-based balancing: block Hadamard transform fused with the quantizer (Sec. 4.2) ----
 
-HADAMARD_SHAPES = [(1, 128), (5, 256), (37, 1152), (130, 4608), (7, 4096), (3, 8192), (9, 2176), (1000, 1152)]
+HADAMARD_SHAPES = [(1, 128), (5, 256), (37, 1152), (130, 4608), (7, 4096), (3, 8192), (9, 2176), (1000, 1152),
+                   (11, 384), (11, 1280), (11, 2304)]
 
 
 @pytest.mark.parametrize("M,K", HADAMARD_SHAPES)

@@ -37,7 +37,8 @@ def say(msg):
 # ---- quantizer -------------------------------------------------------------------------
 
 QUANT_SHAPES = [(1, 8), (5, 64), (37, 1152), (130, 4608), (7, 4096), (3, 8192), (9, 2048),
-                (2, 333), (3, 1), (2, 9000), (4, 8200), (1000, 1152), (6, 520), (3, 3584), (2, 5000)]
+                (2, 333), (3, 1), (2, 9000), (4, 8200), (1000, 1152), (6, 520), (3, 3584), (2, 5000),
+                (11, 384), (11, 1280), (11, 2304)]  # the last three: 16 / 32 / 64 lanes per token, ragged or not
 
 
 @pytest.mark.parametrize("M,K", QUANT_SHAPES)
