@@ -202,3 +202,30 @@ def test_binding_refuses_host_tensors():
     import paper_2406_02540_amd as pkg
     with pytest.raises(TypeError):
         pkg.vq_quantize_per_token(torch.zeros((2, 8), dtype=torch.float16))
+
+
+def test_lane_group_choice(tmp_path):
+    """vq_lanes.h (plain C++): how many lanes share a token whose row is held in fp32 registers."""
+    import subprocess
+    src = tmp_path / "lanes.cpp"
+    src.write_text('#include <cstdio>\n#include "vq_lanes.h"\n'
+                   'int main() { for (int k8 = 1; k8 <= 1024; ++k8) std::printf("%d %d\\n", k8, vq::lanes_for_row(k8)); }\n')
+    exe = tmp_path / "lanes"
+    subprocess.run(["g++", "-O1", "-I", os.path.join(ROOT, "paper_2406_02540_amd", "csrc"), str(src), "-o", str(exe)],
+                   check=True)
+    got = dict(map(int, line.split()) for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                                 text=True).stdout.splitlines())
+    # the shapes of the workloads: K = 1152 -> 32 lanes x 5 chunks, K = 4608 / 4096 -> a whole wavefront
+    assert got[144] == 32 and got[576] == 64 and got[512] == 64 and got[1024] == 64
+    # short rows that only a narrow group divides well
+    assert got[48] == 16 and got[16] == 16 and got[1] == 16 and got[160] == 32
+    for k8, lanes in got.items():
+        assert lanes in (16, 32, 64)
+        nch = -(-k8 // lanes)
+        assert nch <= 16, (k8, lanes)                      # the kernels are instantiated for 1..16 chunks per lane
+        idle = nch * lanes - k8
+        for wider in (l for l in (32, 64) if l > lanes):   # a wider group was passed over only for its idle lanes
+            n2 = -(-k8 // wider)
+            assert n2 > 16 or (n2 * wider - k8) * 100 > 15 * n2 * wider
+        if idle * 100 > 15 * nch * lanes:                  # nothing met the bar: the fewest idle lanes won
+            assert all(-(-k8 // l) > 16 or (-(-k8 // l)) * l - k8 >= idle for l in (16, 32, 64))
