@@ -42,9 +42,10 @@ def assert_f16_gemm_close(got, ref, x, w, K):
     bound = 2.0 ** -10 * np.abs(ref.astype(np.float64)) + K * 2.0 ** -24 * s_abs + 2.0 ** -24
     err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
     assert np.all(err <= bound), f"worst excess {(err - bound).max():.3e}"
-    # and nearly all outputs are the oracle's exactly or its fp16 neighbour
+    # and nearly all outputs are the oracle's exactly or its fp16 neighbour (a handful may sit two
+    # steps away where the fp32 sum lands on the other side of a rounding boundary)
     ulp = np.abs(np.spacing(ref.astype(np.float16))).astype(np.float64)
-    assert (err <= ulp).mean() > 0.999
+    assert (err > ulp).sum() <= max(2, 1e-3 * err.size)
 
 
 F16_SHAPES = [(1, 8, 8), (5, 7, 64), (300, 200, 384), (256, 256, 128), (257, 264, 72), (513, 520, 200),
