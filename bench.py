@@ -43,6 +43,9 @@ def parse():
                    help="skip the measured ceilings (register-only MFMA loop on realistic operands, copy kernel)")
     p.add_argument("--no-fused", action="store_true",
                    help="skip the timings of the fused quantizers and of the FP16 / static comparison kernels")
+    p.add_argument("--graph", action="store_true",
+                   help="replay a HIP graph of the step instead of launching its kernels one by one from the host "
+                        "(measured: no difference, the device queue never runs dry at these kernel durations)")
     p.add_argument("--copy-calibration", action="store_true",
                    help="only run a plain 1 GiB device copy a few times (reference for the "
                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -222,6 +225,20 @@ def main():
         for L in layers:
             vq.vq_linear(L["x"], L["cm"], L["wq"], L["spec"].w_bits, L["ws"], L["bias"], y=L["y"],
                          workspace=L["work"])
+
+    # One step as a HIP graph (the library's calls only enqueue kernels, so they capture as they are):
+    # ten dependent launches replayed as one submission, without the host's launch path between them.
+    if args.graph:
+        eager_step = step
+        eager_step()  # the library's per-device set-up happens outside the capture
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                eager_step()
+        torch.cuda.synchronize()
+        step = graph.replay
 
     # ---- the timed region: W warm-up steps, then exactly K steps --------------------------------
     for _ in range(args.warmup):
@@ -448,7 +465,8 @@ def main():
         "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": workload_name, "layers": [f"{s.name}:{s.M}x{s.K}->{s.N}/w{s.w_bits}" for s in specs],
-                   "ops_per_step": total_ops},
+                   "ops_per_step": total_ops,
+                   "launch": "HIP graph of the step, replayed" if args.graph else "per-call from the host"},
         "frac_of_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": roofline,
         "roofline_quantizer": roofline_q,
