@@ -301,6 +301,23 @@ def main():
                       peak=HBM_PEAK_GBS, unit="GB/s", frac=round(q_achieved / HBM_PEAK_GBS, 4), traffic=None,
                       launches="the %d quantizer launches with M >= 1024, bytes = 3MK + 4M (+4K) each" % len(big))
 
+    def timed(fn, filler=None):
+        # filler: a long launch enqueued behind every timed one, so that the host stays ahead of the
+        # device and the events bracket the kernel alone, not the host's launch path
+        for _ in range(2):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nrep)]
+        for a, b in evs:
+            a.record(); fn(); b.record()
+            if filler is not None:
+                filler()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+
+    def gemm_of(L):
+        f = vq.vq_gemm_w8a8 if L["spec"].w_bits == 8 else vq.vq_gemm_w4a8
+        return lambda: f(L["xq"], L["xs"], L["wq"], L["ws"], L["bias"], y=L["y"])
+
     # ---- the quantizer fused behind its producer, on the same activations ----------------------
     # (not part of the step: LayerNorm + modulation feeds qkv and fc1, GELU feeds fc2, the residual
     # add feeds the next block; bytes = what such a kernel must move, 3MK + 4M, residual 7MK + 4M)
@@ -324,14 +341,16 @@ def main():
                         ("hadamard_quantize", 3, lambda: vq.vq_hadamard_quantize(L["x"], L["cm"], xq=L["xq"], x_scale=L["xs"]))]
             else:
                 runs = [("layernorm_quantize", 3, lambda: vq.vq_layernorm_quantize(L["x"], mod[0], mod[1], T, 1e-6, L["cm"], xq=L["xq"], x_scale=L["xs"]))]
+            if L["cm"] is None:
+                # the plain quantizer with Eq. 3's mask folded in (the step above follows the config to the letter
+                # and has none): the mask is calibrated on the device from these activations and weights, alpha 0.5
+                w32 = torch.from_numpy(L["data"].w).cuda()
+                _, cm_eq3 = vq.vq_balance_mask(vq.vq_channel_absmax(L["x"]), vq.vq_channel_absmax(w32), 0.5)
+                del w32
+                runs.append(("quantize_per_token+eq3_mask", 3,
+                             lambda: vq.vq_quantize_per_token(L["x"], cm_eq3, xq=L["xq"], x_scale=L["xs"])))
             for name, bpe, fn in runs:
-                for _ in range(2):
-                    fn()
-                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nrep)]
-                for a, b in evs:
-                    a.record(); fn(); b.record()
-                torch.cuda.synchronize()
-                dt = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+                dt = timed(fn, filler=gemm_of(L))
                 nbytes = bpe * s.M * s.K + 4 * s.M
                 fused.append(dict(kernel=name, feeds=s.name, M=s.M, K=s.K, us=round(dt * 1e6, 2),
                                   GBps=round(nbytes / dt / 1e9, 1), frac_of_hbm_peak=round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4)))
@@ -340,18 +359,6 @@ def main():
     # ---- the paper's comparison points on the same device (Sec. 5.3): FP16 layers, static W8A8 ---------
     comparison = None
     if not args.no_fused:
-        def timed(fn, filler=None):
-            # filler: a long launch enqueued behind every timed one, so that the host stays ahead of the
-            # device and the events bracket the kernel alone, not the host's launch path
-            for _ in range(2):
-                fn()
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nrep)]
-            for a, b in evs:
-                a.record(); fn(); b.record()
-                if filler is not None:
-                    filler()
-            torch.cuda.synchronize()
-            return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
         rows = []
         for L, pl in zip(layers, per_layer):
             s = L["spec"]
@@ -359,9 +366,7 @@ def main():
                 continue
             w16 = torch.from_numpy(L["data"].w.astype(np.float16)).cuda()
             t16 = timed(lambda: vq.vq_gemm_f16(L["x"], w16, L["bias"], y=L["y"]))
-            gemm = vq.vq_gemm_w8a8 if s.w_bits == 8 else vq.vq_gemm_w4a8
-            ts = timed(lambda: vq.vq_quantize_static(L["x"], 0.05, L["cm"], xq=L["xq"]),
-                       filler=lambda: gemm(L["xq"], L["xs"], L["wq"], L["ws"], L["bias"], y=L["y"]))
+            ts = timed(lambda: vq.vq_quantize_static(L["x"], 0.05, L["cm"], xq=L["xq"]), filler=gemm_of(L))
             tq, tg = pl["quant_us"] * 1e-6, pl["gemm_us"] * 1e-6
             # The vendor library's GEMMs on the same operands, as context for the two hand-written ones
             # (torch's matmuls call hipBLASLt / rocBLAS): the int8 one returns raw int32 sums (no
