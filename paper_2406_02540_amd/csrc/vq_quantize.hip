@@ -3,7 +3,8 @@
 // 1. Dynamic per-token activation quantizer (ViDiT-Q Sec. 4.1; Eq. 2 of Sec. 3.1
 //    in symmetric form; activation side of the channel balancing, Eq. 3 of
 //    Sec. 4.2).  HBM-bound: a token is read once (2 B/element), kept in
-//    registers as fp32 across the absmax reduction, and written once
+//    registers across the absmax reduction (as the fp16 it arrived as, or as
+//    fp32 products where a balancing factor is folded in), and written once
 //    (1 B/element + one fp32 scale).
 // 2. Offline per-output-channel weight quantizer (same recipe, qmax 127 or 7,
 //    weight side of Eq. 3), with the 4-bit packer fused.
@@ -23,10 +24,9 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
-// The token row held in registers (layout and steps: vq_quantize_row.h).  LANES is chosen
-// so that K / 8 = NCH * LANES exactly where possible (K = 1152: 16 lanes x 9 chunks),
-// which keeps every lane busy on every instruction.  This instantiation folds the
-// balancing factor in as the row arrives and keeps the products in fp32.
+// The token row held in registers (layout and steps: vq_quantize_row.h).  This kernel folds
+// the balancing factor in as the row arrives and keeps the products in fp32: 8 registers per
+// chunk, so the launcher prefers few chunks per lane (K = 1152: 32 lanes x 5 chunks).
 template <int NCH, int LANES>
 __global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave_mul(
     const half8* __restrict__ x, const float4v* __restrict__ chan_mul, int2v* __restrict__ xq,
@@ -41,7 +41,9 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_tokens_wave_mul(
 // 512 registers per SIMD lane).
 constexpr int quant_waves(int nch) { return nch <= 10 ? 8 : nch == 11 ? 7 : nch == 12 ? 6 : nch <= 15 ? 5 : 4; }
 
-// No balancing factor: the row stays in registers as the fp16 it arrived as (half the
+// No balancing factor: LANES is chosen so that K / 8 = NCH * LANES exactly where possible
+// (K = 1152: 16 lanes x 9 chunks), which keeps every lane busy on every instruction, and
+// the row stays in registers as the fp16 it arrived as (half the
 // registers of an fp32 copy, so that twice as many wavefronts are resident and every
 // workgroup of the video-sized problem is in flight at once).  The absolute maximum is
 // taken on the fp16 values (exact: fp16 -> fp32 is monotonic and exact), each value is
