@@ -271,10 +271,13 @@ def main():
     per_layer = []
     for i, L in enumerate(layers):
         s = L["spec"]
-        tq = float(np.mean([ev[r][i][0].elapsed_time(ev[r][i][1]) for r in range(nrep)])) * 1e-3
-        tg = float(np.mean([ev[r][i][1].elapsed_time(ev[r][i][2]) for r in range(nrep)])) * 1e-3
+        tqs = np.array([ev[r][i][0].elapsed_time(ev[r][i][1]) for r in range(nrep)]) * 1e-3
+        tgs = np.array([ev[r][i][1].elapsed_time(ev[r][i][2]) for r in range(nrep)]) * 1e-3
+        tq, tg = float(tqs.mean()), float(tgs.mean())
         per_layer.append(dict(layer=s.name, M=s.M, K=s.K, N=s.N, w_bits=s.w_bits,
                               quant_us=tq * 1e6, gemm_us=tg * 1e6,
+                              gemm_us_median=float(np.median(tgs)) * 1e6, gemm_us_min=float(tgs.min()) * 1e6,
+                              quant_us_median=float(np.median(tqs)) * 1e6, quant_us_min=float(tqs.min()) * 1e6,
                               quant_GBps=quant_bytes(s, L["cm"] is not None) / tq / 1e9,
                               gemm_TOPS=s.ops / tg / 1e12,
                               gemm_frac_of_peak=s.ops / tg / 1e12 / INT8_MFMA_PEAK_TOPS,
