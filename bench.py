@@ -318,12 +318,16 @@ def main():
     def timed_batch(fns, reps=None):
         """Seconds per pass over fns (short kernels).  A pair of events around one 20 us launch adds 2-4 us that are
         not the kernel's (the kernel trace shows its duration without them), so the launches go back to back between
-        ONE pair of events; a few long GEMMs enqueued first give the host the head start to keep the queue full."""
+        ONE pair of events; long GEMMs enqueued first give the host the head start to keep the queue full."""
         reps = reps or nrep
         for f in fns:
             f()
-        head = gemm_of(max(layers, key=lambda L: L["spec"].ops))
-        for _ in range(4):
+        # head start: enough GEMM time in the queue for the host to enqueue every timed launch (about 25 us each,
+        # generously) before the device reaches the first of them
+        hi = max(range(len(layers)), key=lambda i: layers[i]["spec"].ops)
+        head = gemm_of(layers[hi])
+        n_head = int(min(400, max(4, np.ceil(reps * len(fns) * 25e-6 / (per_layer[hi]["gemm_us"] * 1e-6)))))
+        for _ in range(n_head):
             head()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
