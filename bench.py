@@ -498,6 +498,11 @@ def main():
                                       "algorithmic_bytes": int(sum(gemm_bytes(L["spec"]) for L, _ in big) / len(big)),
                                       "per": "launch, average over the %d large layers" % len(big),
                                       "source": t["source"]}
+    qtrace_file = os.path.join(ROOT, "profiles", "quantizer_trace_video_w8a8.json")
+    if args.workload == "video" and os.path.exists(qtrace_file):
+        # the kernel's own durations inside the steps, from the committed rocprofv3 kernel trace of this command
+        # (events cannot leave out the gaps between launches, which weigh on a 20 us kernel)
+        roofline_q["kernel_trace"] = json.load(open(qtrace_file))
     if ceilings:
         roofline["measured_mfma_only_ceiling"] = ceilings["mfma_only_tops_activation_like_x_weight_like"]
         roofline["frac_of_measured_ceiling"] = round(
