@@ -322,11 +322,11 @@ def main():
         reps = reps or nrep
         for f in fns:
             f()
-        # head start: enough GEMM time in the queue for the host to enqueue every timed launch (about 25 us each,
+        # head start: enough GEMM time in the queue for the host to enqueue every timed launch (about 15 us each,
         # generously) before the device reaches the first of them
         hi = max(range(len(layers)), key=lambda i: layers[i]["spec"].ops)
         head = gemm_of(layers[hi])
-        n_head = int(min(400, max(4, np.ceil(reps * len(fns) * 25e-6 / (per_layer[hi]["gemm_us"] * 1e-6)))))
+        n_head = int(min(400, max(4, np.ceil(reps * len(fns) * 15e-6 / (per_layer[hi]["gemm_us"] * 1e-6)))))
         for _ in range(n_head):
             head()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
