@@ -1,7 +1,8 @@
 // Measured ceilings of the device the library runs on, printed as one JSON object:
 //   - register-only v_mfma_i32_32x32x32_i8 loop (no memory traffic at all) for several operand
 //     distributions: the sustained matrix-core rate depends on the operand data on this part,
-//     so the nominal int8 peak is not what a GEMM on realistic data can be measured against;
+//     so the nominal int8 peak is not what a GEMM on realistic data can be measured against
+//     (and, for one distribution, the same loop of v_mfma_i32_16x16x64_i8);
 //   - a plain device-to-device copy kernel (HBM bandwidth ceiling for the quantizer).
 // Stand-alone program (hipcc --offload-arch=gfx950); bench.py --ceilings runs it.
 #include <hip/hip_runtime.h>
@@ -46,6 +47,31 @@ __global__ __launch_bounds__(kThreads) void mfma_only(const v4i* data, int* out,
     int sum = 0;
     for (int i = 0; i < 8; ++i)
         for (int r = 0; r < 16; ++r) sum += acc[i][r];
+    if (sum == 0x12345678) out[0] = sum;  // keeps the loop alive
+}
+
+// The same loop with the other int8 shape (16 x 16 x 64: as many operations per second of
+// matrix pipe, half the accumulator registers moved per operation).
+__global__ __launch_bounds__(kThreads) void mfma_only_16x16x64(const v4i* data, int* out, int iters) {
+    v4i a[kSets], b[kSets];
+    for (int s = 0; s < kSets; ++s) {
+        a[s] = data[(2 * s) * kThreads + threadIdx.x];
+        b[s] = data[(2 * s + 1) * kThreads + threadIdx.x];
+    }
+    v4i acc[16];
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 4; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < kSets; ++s)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[(s + (i >> 2)) % kSets], b[(s + i) % kSets], acc[i], 0,
+                                                               0, 0);
+    }
+    int sum = 0;
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 4; ++r) sum += acc[i][r];
     if (sum == 0x12345678) out[0] = sum;  // keeps the loop alive
 }
 
@@ -109,6 +135,20 @@ int main() {
         ms /= reps;
         const double ops = (double)cus * (kThreads / 64) * iters * kSets * 8 * 2.0 * 32 * 32 * 32;
         printf(", \"mfma_only_tops_%s\": %.0f", names[mode], ops / ms / 1e9);
+        if (mode == 2) {  // the other shape on the same operands (16 MFMAs of half the size per set)
+            for (int rep = 0; rep < 10; ++rep)
+                hipLaunchKernelGGL(mfma_only_16x16x64, dim3(cus), dim3(kThreads), 0, 0, (const v4i*)d, out, iters);
+            CK(hipDeviceSynchronize());
+            CK(hipEventRecord(e0));
+            for (int rep = 0; rep < reps; ++rep)
+                hipLaunchKernelGGL(mfma_only_16x16x64, dim3(cus), dim3(kThreads), 0, 0, (const v4i*)d, out, iters);
+            CK(hipEventRecord(e1));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            ms /= reps;
+            const double ops16 = (double)cus * (kThreads / 64) * iters * kSets * 16 * 2.0 * 16 * 16 * 64;
+            printf(", \"mfma_only_tops_16x16x64_%s\": %.0f", names[mode], ops16 / ms / 1e9);
+        }
     }
 
     // ---- copy --------------------------------------------------------------------------
