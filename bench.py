@@ -344,17 +344,20 @@ def main():
     def quantizer_of(L):
         return lambda: vq.vq_quantize_per_token(L["x"], L["cm"], xq=L["xq"], x_scale=L["xs"])
     q_time = timed_batch([quantizer_of(L) for L, _ in big])
-    q_achieved = q_bytes / q_time / 1e9
+    # Three readings of the same launches: each between its own pair of events inside the step (includes the
+    # 2-3 us between a GEMM and the next launch: conservative, and the conditions of the timed region), all of them
+    # back to back between one pair of events (no GEMMs in between: a long run of memory-bound launches), and the
+    # kernel's own durations in the committed rocprofv3 trace of this command (added below).
+    q_achieved = q_bytes / q_time_in_step / 1e9
     roofline_q = dict(kernel="quantize_tokens_wave", bound="hbm", achieved=round(q_achieved, 1),
                       peak=HBM_PEAK_GBS, unit="GB/s", frac=round(q_achieved / HBM_PEAK_GBS, 4), traffic=None,
-                      launches="the %d quantizer launches with M >= 1024 (distinct inputs, %.0f MB), back to back between one "
-                               "pair of HIP events, %d passes; bytes = 3MK + 4M (+4K) each"
-                               % (len(big), sum(2 * L["spec"].M * L["spec"].K for L, _ in big) / 1e6, nrep),
-                      in_step_GBps=round(q_bytes / q_time_in_step / 1e9, 1),
-                      in_step_note="the same launches inside the step, each between its own pair of events "
-                                   "(includes the gap behind the preceding GEMM)")
-    log(f"quantizer, {len(big)} launches back to back: {q_time * 1e6:.1f} us per pass, {q_achieved:.0f} GB/s "
-        f"(inside the step, event pair per launch: {q_bytes / q_time_in_step / 1e9:.0f} GB/s)")
+                      launches="the %d quantizer launches with M >= 1024 inside the step, each between its own pair of HIP "
+                               "events; bytes = 3MK + 4M (+4K) each" % len(big),
+                      back_to_back_GBps=round(q_bytes / q_time / 1e9, 1),
+                      back_to_back_note="the same launches (distinct inputs, %.0f MB) back to back between one pair of "
+                                        "events, %d passes" % (sum(2 * L["spec"].M * L["spec"].K for L, _ in big) / 1e6, nrep))
+    log(f"quantizer, {len(big)} launches: {q_achieved:.0f} GB/s inside the step (event pair per launch), "
+        f"{q_bytes / q_time / 1e9:.0f} GB/s back to back")
 
     # ---- the quantizer fused behind its producer, on the same activations ----------------------
     # (not part of the step: LayerNorm + modulation feeds qkv and fc1, GELU feeds fc2, the residual
