@@ -191,11 +191,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
     // One quarter of a stage's loads (this wave's share): issued between the K steps of
     // the stage being multiplied, so that no wave sits in a queue of eight loads.
     auto issue_part = [&](const TileLoads& ld, int buf, int k0, int j) {
-        load_to_lds_16(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
+        load_stage_to_lds_16<K_TAIL>(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
         if (W_BITS != 4)
-            load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j], k0);
+            load_stage_to_lds_16<K_TAIL>(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j], k0);
         else if (j < 2)
-            load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
+            load_stage_to_lds_16<K_TAIL>(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
                            k0 / 2);
     };
 
@@ -205,9 +205,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a)
         const int j = (W_BITS != 4 || s < 4) ? (s >> 1) : (s - 2);
         const bool is_w = (W_BITS != 4 || s < 4) ? (s & 1) : false;
         if (!is_w)
-            load_to_lds_16(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
+            load_stage_to_lds_16<K_TAIL>(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
         else
-            load_to_lds_16(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
+            load_stage_to_lds_16<K_TAIL>(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
                            W_BITS != 4 ? k0 : k0 / 2);
     };
 

@@ -56,6 +56,18 @@ __device__ __forceinline__ void load_to_lds_16(v4i rsrc, unsigned lds_addr, int 
         : "memory");
 }
 
+// The same for a stage at byte k0 of the rows.  K a multiple of the stage: k0 rides in the scalar
+// offset.  Otherwise (the last stage reaches past K) it is added to the per-lane offset, the part
+// of the address that the buffer's range check looks at: 16-byte pieces past the end of the last
+// row of the buffer then read as zero instead of touching memory behind it.
+template <bool K_TAIL>
+__device__ __forceinline__ void load_stage_to_lds_16(v4i rsrc, unsigned lds_addr, int voff, int k0) {
+    if (K_TAIL)
+        load_to_lds_16(rsrc, lds_addr, voff + k0, 0);
+    else
+        load_to_lds_16(rsrc, lds_addr, voff, k0);
+}
+
 // Waits until all of this wave's direct loads (and stores) have completed and all
 // its LDS accesses are done, then joins the workgroup barrier.
 __device__ __forceinline__ void wait_loads_and_barrier() {

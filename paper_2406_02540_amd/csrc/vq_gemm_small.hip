@@ -82,13 +82,13 @@ __global__ __launch_bounds__(kThreadsS) void gemm_i8_dequant_small(const SmallAr
     auto issue_stage = [&](int slot, int k0) {
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-            load_to_lds_16(rsrc_x, lds_x_addr + slot * kXS + (wave + 4 * j) * 1024, voff_x[j], k0);
+            load_stage_to_lds_16<K_TAIL>(rsrc_x, lds_x_addr + slot * kXS + (wave + 4 * j) * 1024, voff_x[j], k0);
         if (W_BITS == 8) {
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                load_to_lds_16(rsrc_w, lds_w_addr + slot * kWS + (wave + 4 * j) * 1024, voff_w[j], k0);
+                load_stage_to_lds_16<K_TAIL>(rsrc_w, lds_w_addr + slot * kWS + (wave + 4 * j) * 1024, voff_w[j], k0);
         } else {
-            load_to_lds_16(rsrc_w, lds_w_addr + slot * kWS + wave * 1024, voff_w[0], k0 / 2);
+            load_stage_to_lds_16<K_TAIL>(rsrc_w, lds_w_addr + slot * kWS + wave * 1024, voff_w[0], k0 / 2);
         }
     };
 
