@@ -202,8 +202,12 @@ int vq_gemm_w4a8(const int8_t* xq, const float* x_scale, const uint8_t* wq4, con
                  int M, int N, int K, void* hip_stream);
 
 /*
- * The whole layer: vq_quantize_per_token into the workspace, then the GEMM that
- * w_bits selects (8: w is int8 [N,K]; 4: w is uint8 [N,K/2] packed as above).
+ * The whole quantized linear layer as the paper deploys it, a composition of the calls
+ * above: the dynamic token-wise quantizer with the balancing factor (Sec. 4.1; Sec. 4.2
+ * Eq. 3) into the workspace, then the integer GEMM with its dequantization (appendix
+ * "Hardware implementation of quantized linear layers") that w_bits selects (8: w is
+ * int8 [N,K]; 4: w is uint8 [N,K/2] packed as above, appendix "Performance of ViDiT-Q
+ * under lower bitwidth").
  *
  *   workspace  device scratch of at least vq_linear_workspace_bytes(M,N,K,w_bits)
  *              bytes, 16-byte aligned; holds xq and x_scale between the two
@@ -213,7 +217,8 @@ int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bit
               const float* w_scale, const void* bias_f16, void* y_f16,
               void* workspace, size_t workspace_bytes, int M, int N, int K, void* hip_stream);
 
-/* Bytes of workspace vq_linear needs (0 if a size is invalid). Host-only, no HIP call. */
+/* Bytes of workspace vq_linear needs (0 if a size is invalid): the int8 activations and
+ * the token scales the quantizer of Sec. 4.1 hands to the GEMM.  Host-only, no HIP call. */
 size_t vq_linear_workspace_bytes(int M, int N, int K, int w_bits);
 
 /*
@@ -231,7 +236,8 @@ size_t vq_linear_workspace_bytes(int M, int N, int K, int w_bits);
 int vq_quantize_weight(const float* w_f32, const float* chan_s, int w_bits, void* wq_out,
                        float* w_scale, int N, int K, void* hip_stream);
 
-/* Static, host-side description of a vq_status value. */
+/* Static, host-side description of a vq_status value (no passage of the paper: the error
+ * reporting of this boundary). */
 const char* vq_status_string(int status);
 
 #ifdef __cplusplus

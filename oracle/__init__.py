@@ -20,6 +20,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "vq_oracle.c")
 _LIB = os.path.join(_HERE, "libvq_oracle.so")
+# A test may point this at another build of the same source (the sanitizer build of
+# tests/test_sanitizers.py); it is then loaded as it is and never rebuilt here.
+_LIB_OVERRIDE = os.environ.get("VQ_ORACLE_LIB")
 
 # No fused multiply-add, no reassociation: every fp32 operation rounds on its own.
 CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
@@ -28,6 +31,8 @@ CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc; returns the path of the shared library."""
+    if _LIB_OVERRIDE:
+        return _LIB_OVERRIDE
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])

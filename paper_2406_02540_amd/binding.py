@@ -13,7 +13,8 @@ import os
 import torch
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(PKG_DIR, "libvidiq.so")
+# the in-tree build; VQ_LIBVIDIQ_PATH names another build of the same sources (e.g. one with host sanitizers)
+LIB_PATH = os.environ.get("VQ_LIBVIDIQ_PATH") or os.path.join(PKG_DIR, "libvidiq.so")
 
 VQ_OK = 0
 STATUS_NAMES = {0: "VQ_OK", 1: "VQ_ERR_NULL", 2: "VQ_ERR_SHAPE", 3: "VQ_ERR_ALIGN",

@@ -4,7 +4,7 @@
 //     so the nominal int8 peak is not what a GEMM on realistic data can be measured against
 //     (and, for one distribution, the same loop of v_mfma_i32_16x16x64_i8);
 //   - a plain device-to-device copy kernel (HBM bandwidth ceiling for the quantizer).
-// Stand-alone program (hipcc --offload-arch=gfx950); bench.py --ceilings runs it.
+// Stand-alone program (hipcc --offload-arch=gfx950); bench.py runs it before its own work unless --no-ceilings is given.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>

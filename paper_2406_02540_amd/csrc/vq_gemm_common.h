@@ -44,8 +44,9 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
 }
 
 // 16 bytes per lane from buffer offset voff + soff straight into LDS at
-// lds_addr + 16 * lane (lds_addr is wave-uniform and goes through M0).  Counts
-// in vmcnt; the compiler does not know about it, see wait_loads_and_barrier().
+// lds_addr + 16 * lane (lds_addr is wave-uniform and goes through M0, which the
+// statement declares as clobbered).  Counts in vmcnt; the compiler does not know
+// about it, see wait_loads_and_barrier().
 __device__ __forceinline__ void load_to_lds_16(v4i rsrc, unsigned lds_addr, int voff, int soff) {
     asm volatile(
         "s_mov_b32 m0, %0\n\t"
@@ -53,7 +54,7 @@ __device__ __forceinline__ void load_to_lds_16(v4i rsrc, unsigned lds_addr, int 
         "buffer_load_dwordx4 %1, %2, %3 offen lds"
         :
         : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-        : "memory");
+        : "memory", "m0");
 }
 
 // The same for a stage at byte k0 of the rows.  K a multiple of the stage: k0 rides in the scalar

@@ -4,8 +4,8 @@ baseline) against the CPU oracle.
 vq_quantize_static is integer work: bit-exact.  vq_gemm_f16 sums exact fp16 products in fp32
 in the matrix cores' order, the oracle in fp64: an output may differ by the fp32 accumulation
 error, at most K * 2^-24 * sum_k |x_k w_k| (every partial sum is bounded by that sum), plus one
-rounding to fp16 on each side:
-    |g - r| <= 2^-10 * |r| + K * 2^-24 * sum_k |x_k w_k| + 2^-24 (fp16 subnormal step).
+rounding to fp16 on each side (half a step of the rounded value):
+    |g - r| <= ulp16(g)/2 + ulp16(r)/2 + K * 2^-24 * sum_k |x_k w_k|.
 """
 import numpy as np
 import pytest
@@ -37,15 +37,20 @@ def say(msg):
     print(msg, flush=True)
 
 
-def assert_f16_gemm_close(got, ref, x, w, K):
+def assert_f16_gemm_close(got, ref, x, w, K, b=None):
+    """|g - r| <= ulp(g)/2 + ulp(r)/2 + K * 2^-24 * (sum_k |x_k w_k| + |b|): the two sides round to fp16 once
+    each (half a step of their own result) and differ before that by the fp32 accumulation error only (K - 1
+    additions of products and one of the bias, each within 2^-24 of a partial sum no larger than the sum of
+    the magnitudes).  How many
+    outputs end up more than one step apart depends on how strongly the products of an output cancel, so no
+    count of such outputs is asserted: the bound above is per element and complete."""
     s_abs = np.abs(x.astype(np.float64)) @ np.abs(w.astype(np.float64)).T
-    bound = 2.0 ** -10 * np.abs(ref.astype(np.float64)) + K * 2.0 ** -24 * s_abs + 2.0 ** -24
+    step = lambda a: np.abs(np.spacing(a.astype(np.float16))).astype(np.float64)  # noqa: E731
+    if b is not None:
+        s_abs = s_abs + np.abs(b.astype(np.float64))[None, :]
+    bound = 0.5 * step(got) + 0.5 * step(ref) + K * 2.0 ** -24 * s_abs
     err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
     assert np.all(err <= bound), f"worst excess {(err - bound).max():.3e}"
-    # and nearly all outputs are the oracle's exactly or its fp16 neighbour (a handful may sit two
-    # steps away where the fp32 sum lands on the other side of a rounding boundary)
-    ulp = np.abs(np.spacing(ref.astype(np.float16))).astype(np.float64)
-    assert (err > ulp).sum() <= max(2, 1e-3 * err.size)
 
 
 F16_SHAPES = [(1, 8, 8), (5, 7, 64), (300, 200, 384), (256, 256, 128), (257, 264, 72), (513, 520, 200),
@@ -63,7 +68,7 @@ def test_gemm_f16(vq, oracle, M, N, K, with_bias):
     ref = oracle.gemm_f16(x, w, b)
     y = vq.vq_gemm_f16(dev(x), dev(w), dev(b))
     torch.cuda.synchronize()
-    assert_f16_gemm_close(host(y), ref, x, w, K)
+    assert_f16_gemm_close(host(y), ref, x, w, K, b)
 
 
 def test_gemm_f16_exact_integers_and_identity(vq):
@@ -88,7 +93,7 @@ def test_gemm_f16_full_size_sampled_rows(vq, oracle):
     y = host(vq.vq_gemm_f16(dev(x), dev(w), dev(b)))
     rows = np.unique(np.concatenate([[0, M - 1], g.integers(0, M, 96)]))
     ref = oracle.gemm_f16(x[rows], w, b)
-    assert_f16_gemm_close(y[rows], ref, x[rows], w, K)
+    assert_f16_gemm_close(y[rows], ref, x[rows], w, K, b)
 
 
 @pytest.mark.parametrize("M,K", [(1, 8), (5, 64), (37, 1152), (9, 333), (3, 1), (130, 4608), (1000, 1152)])

@@ -190,6 +190,36 @@ def test_identity_weights_select_the_activations(vq):
     assert np.array_equal(host(y).astype(np.int32), xq.astype(np.int32))  # |values| < 2048: exact in fp16
 
 
+@pytest.mark.parametrize("bits,K", [(8, 4608), (4, 4608), (8, 1168), (4, 1184)])
+def test_line_store_variant_shows_its_integer_sums(vq, oracle, bits, K):
+    """The kernel variant the benchmark times (no copy of the sums, whole-line stores, and, at
+    these sizes, the persistent large-tile kernel: 12 x 12 tiles) against the oracle's integer
+    sums without the element-store variant in between: activations sparse in {-1, 0, 1} keep
+    every sum below 2048 in magnitude, so with unit scales and no bias the fp16 output IS the
+    integer sum (appendix "Hardware implementation of quantized linear layers": integer sum
+    first, scales afterwards).  K = 4608 is a whole number of K stages, the other K is not."""
+    say(f"gemm w{bits}a8 line-store variant, exact integers, K={K}")
+    M, N = 2900, 2824
+    g = np.random.default_rng(4100 + bits + K)
+    qmax = 127 if bits == 8 else 7
+    nnz = 2047 // qmax if bits == 8 else 250          # |sum| <= nnz * qmax < 2048
+    xq = np.zeros((M, K), np.int8)
+    cols = np.argsort(g.random((M, K)), axis=1)[:, :nnz]   # nnz distinct positions per token, all of K covered
+    xq[np.arange(M)[:, None], cols] = g.choice(np.array([-1, 1], np.int8), (M, nnz))
+    wq = g.integers(-qmax, qmax + 1, (N, K), dtype=np.int8)
+    acc_ref = oracle.gemm_i8(xq, wq)
+    assert np.abs(acc_ref).max() < 2048 and np.abs(acc_ref).max() > 256
+    one_m, one_n = dev(np.ones(M, np.float32)), dev(np.ones(N, np.float32))
+    if bits == 8:
+        y = vq.vq_gemm_w8a8(dev(xq), one_m, dev(wq), one_n)
+    else:
+        y = vq.vq_gemm_w4a8(dev(xq), one_m, dev(oracle.pack_int4(wq)), one_n)
+    torch.cuda.synchronize()
+    got = host(y).astype(np.float32)
+    assert np.array_equal(got, acc_ref.astype(np.float32)), \
+        f"{int((got != acc_ref).sum())} of {got.size} integer sums differ"
+
+
 def test_runs_are_bitwise_repeatable_and_streams_are_honoured(vq, oracle):
     say("determinism / stream")
     g = np.random.default_rng(88)
