@@ -44,7 +44,8 @@ typedef enum vq_status {
     VQ_ERR_SHAPE = 2,     /* negative size, K == 0, K too large, or K not a multiple
                              of what the entry point requires                         */
     VQ_ERR_ALIGN = 3,     /* a base pointer is not 16-byte aligned                    */
-    VQ_ERR_WORKSPACE = 4, /* workspace smaller than vq_linear_workspace_bytes()       */
+    VQ_ERR_WORKSPACE = 4, /* workspace smaller than vq_linear_workspace_bytes(), or that
+                             size beyond VQ_LINEAR_STATIC_SCRATCH_BYTES (vq_linear_static) */
     VQ_ERR_LAUNCH = 5,    /* the HIP runtime refused the launch                       */
     VQ_ERR_ARCH = 6,      /* the current device is not gfx950 (or there is no device) */
     VQ_ERR_BITS = 7       /* w_bits is neither 8 nor 4                                */
@@ -220,6 +221,28 @@ int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bit
 /* Bytes of workspace vq_linear needs (0 if a size is invalid): the int8 activations and
  * the token scales the quantizer of Sec. 4.1 hands to the GEMM.  Host-only, no HIP call. */
 size_t vq_linear_workspace_bytes(int M, int N, int K, int w_bits);
+
+/*
+ * vq_linear without a workspace argument, for callers that cannot allocate device memory
+ * around the call (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc).  The int8 activations and token scales live in a scratch array built into the
+ * library, VQ_LINEAR_STATIC_SCRATCH_BYTES per device, held until the process ends; the call
+ * itself allocates and frees nothing.  Same kernels, same results as vq_linear.
+ *
+ *   - VQ_ERR_WORKSPACE if vq_linear_workspace_bytes(M,N,K,w_bits) exceeds
+ *     VQ_LINEAR_STATIC_SCRATCH_BYTES (e.g. 32768 x 1152 and 8192 x 4608 activations fit,
+ *     32768 x 4608 do not); VQ_ERR_LAUNCH if the scratch array cannot be located.
+ *   - Every call on a device uses that device's one array: calls that may overlap in time
+ *     on one device (different streams, different threads) race on it and must be ordered
+ *     by the caller.  Nothing in the array has to start at zero; it keeps the last call's
+ *     contents.
+ *   - The first call on a device looks the array's address up (once per device); make that
+ *     call outside any stream capture.
+ */
+#define VQ_LINEAR_STATIC_SCRATCH_BYTES (40u << 20)
+int vq_linear_static(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
+                     const float* w_scale, const void* bias_f16, void* y_f16,
+                     int M, int N, int K, void* hip_stream);
 
 /*
  * Offline side: per-output-channel symmetric weight quantizer (Sec. 4.1: one

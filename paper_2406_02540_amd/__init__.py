@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     vq_gemm_w8a8,
     vq_layernorm_quantize,
     vq_linear,
+    vq_linear_static,
     vq_linear_workspace_bytes,
     vq_quantize_per_token,
     vq_quantize_static,

@@ -37,6 +37,7 @@ SIGNATURES = {
     "vq_gemm_w4a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
     "vq_linear": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
     "vq_linear_workspace_bytes": (_SZ, [_I, _I, _I, _I]),
+    "vq_linear_static": (_I, [_P, _P, _P, _I, _P, _P, _P, _I, _I, _I, _P]),
     "vq_quantize_weight": (_I, [_P, _P, _I, _P, _P, _I, _I, _P]),
     "vq_status_string": (ctypes.c_char_p, [_I]),
 }
@@ -318,8 +319,10 @@ def vq_linear_workspace_bytes(M, N, K, w_bits) -> int:
     return int(lib().vq_linear_workspace_bytes(int(M), int(N), int(K), int(w_bits)))
 
 
-def vq_linear(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, workspace=None, stream=None):
-    """The whole layer on fp16 activations; workspace is a uint8 device tensor (allocated if None)."""
+LINEAR_STATIC_SCRATCH_BYTES = 40 << 20  # VQ_LINEAR_STATIC_SCRATCH_BYTES of include/vq.h
+
+
+def _linear_args(x, chan_mul, w, w_bits, w_scale, bias, y, where):
     x = _dev(x, torch.float16, "x")
     M, K = x.shape
     if w_bits == 8:
@@ -329,7 +332,7 @@ def vq_linear(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, workspace=None
         w = _dev(w, torch.uint8, "w")
         ok = K % 2 == 0 and tuple(w.shape[1:]) == (K // 2,)
     else:
-        raise VqError(7, "vq_linear")
+        raise VqError(7, where)
     if not ok:
         raise ValueError("weight shape does not match K")
     N = w.shape[0]
@@ -344,6 +347,22 @@ def vq_linear(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, workspace=None
     _dev(y, torch.float16, "y")
     if tuple(y.shape) != (M, N):
         raise ValueError("y shape")
+    return x, chan_mul, w, w_scale, bias, y, M, N, K
+
+
+def vq_linear_static(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, stream=None):
+    """The whole layer with the library's built-in scratch instead of a workspace (the call allocates nothing
+    when y is given); layers whose int8 activations exceed LINEAR_STATIC_SCRATCH_BYTES raise VQ_ERR_WORKSPACE."""
+    x, chan_mul, w, w_scale, bias, y, M, N, K = _linear_args(x, chan_mul, w, w_bits, w_scale, bias, y,
+                                                             "vq_linear_static")
+    _check(lib().vq_linear_static(_ptr(x), _ptr(chan_mul), _ptr(w), int(w_bits), _ptr(w_scale), _ptr(bias),
+                                  _ptr(y), M, N, K, _stream(stream)), "vq_linear_static")
+    return y
+
+
+def vq_linear(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, workspace=None, stream=None):
+    """The whole layer on fp16 activations; workspace is a uint8 device tensor (allocated if None)."""
+    x, chan_mul, w, w_scale, bias, y, M, N, K = _linear_args(x, chan_mul, w, w_bits, w_scale, bias, y, "vq_linear")
     need = vq_linear_workspace_bytes(M, N, K, w_bits)
     if workspace is None:
         workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=x.device)

@@ -12,6 +12,30 @@ constexpr int kMaxDevices = 64;
 
 inline bool misaligned(const void* p) { return ((uintptr_t)p % kAlign) != 0; }
 
+// Scratch of vq_linear_static: the int8 activations and the token scales between its two
+// kernels.  One copy per device that loads the library, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; the address kernels are given is the
+// one that call returns (static_scratch() below).
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[VQ_LINEAR_STATIC_SCRATCH_BYTES];
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// The current device's copy of `scratch`, looked up once per device; nullptr on failure.
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
+
 // 0 = not looked at yet, 1 = gfx950, 2 = something else.  A benign cache: the
 // answer for a device ordinal never changes during the life of the process.
 std::atomic<int> g_arch_state[kMaxDevices];
@@ -267,6 +291,33 @@ int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bit
                                          M, N, K, num_cus, stream));
 }
 
+int vq_linear_static(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
+                     const float* w_scale, const void* bias_f16, void* y_f16, int M, int N, int K,
+                     void* hip_stream) {
+    if (w_bits != 8 && w_bits != 4) return VQ_ERR_BITS;
+    if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K) return VQ_ERR_SHAPE;
+    if (K % (w_bits == 8 ? 16 : 32) != 0) return VQ_ERR_SHAPE;
+    if (M == 0 || N == 0) return VQ_OK;
+    if (vq_linear_workspace_bytes(M, N, K, w_bits) > (size_t)VQ_LINEAR_STATIC_SCRATCH_BYTES)
+        return VQ_ERR_WORKSPACE;
+    int num_cus = 0;
+    const int arch = check_arch(&num_cus);
+    if (arch != VQ_OK) return arch;
+    void* const ws = static_scratch();
+    if (!ws) return VQ_ERR_LAUNCH;
+    int8_t* xq = (int8_t*)ws;
+    float* x_scale = (float*)((char*)ws + round_up((size_t)M * (size_t)K, kAlign));
+    int v = validate_quantize(x_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    v = validate_gemm(xq, x_scale, w, w_scale, bias_f16, y_f16, nullptr, w_bits, M, N, K);
+    if (v != VQ_OK) return v;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    v = launch_status(vq::launch_quantize_per_token(x_f16, chan_mul, xq, x_scale, M, K, stream));
+    if (v != VQ_OK) return v;
+    return launch_status(vq::launch_gemm(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, nullptr,
+                                         M, N, K, num_cus, stream));
+}
+
 int vq_quantize_weight(const float* w_f32, const float* chan_s, int w_bits, void* wq_out,
                        float* w_scale, int N, int K, void* hip_stream) {
     if (w_bits != 8 && w_bits != 4) return VQ_ERR_BITS;
@@ -289,7 +340,7 @@ const char* vq_status_string(int status) {
         case VQ_ERR_NULL: return "a required pointer is NULL";
         case VQ_ERR_SHAPE: return "invalid or unsupported M, N or K";
         case VQ_ERR_ALIGN: return "a pointer is not 16-byte aligned";
-        case VQ_ERR_WORKSPACE: return "workspace too small";
+        case VQ_ERR_WORKSPACE: return "workspace too small (or the layer exceeds the built-in scratch)";
         case VQ_ERR_LAUNCH: return "kernel launch failed";
         case VQ_ERR_ARCH: return "current device is not gfx950";
         case VQ_ERR_BITS: return "w_bits must be 8 or 4";
