@@ -1,510 +1,33 @@
-// int8 x int8 -> int32 MFMA GEMM with the dequantization epilogue, for gfx950.
-//
-// Computes, for tokens m and output channels n (ViDiT-Q appendix "Hardware
-// implementation of quantized linear layers"; Sec. 4.1 for the grouping):
-//     acc[m,n] = sum_k xq[m,k] * wq[n,k]
-//     y[m,n]   = fp16(float(acc) * x_scale[m] * w_scale[n] + bias[n])
-// W4A8 (appendix "Performance under lower bitwidth"): 4-bit weights are staged
-// in LDS packed and widened to int8 on their way from LDS into the MFMA operand
-// registers; the mainloop is otherwise the same.
-//
-// Shape of the kernel
-//   - workgroup tile: 256 tokens x 256 output channels, 8 wavefronts (2 x 4),
-//     each wavefront 128 tokens x 64 channels = 2 x 4 MFMA 32x32x32 blocks,
-//     128 int32 accumulators per lane, two wavefronts per SIMD.  The tile is
-//     large because the L2 -> CU path, not HBM, is what the operand traffic
-//     loads: bytes per multiply-add fall with the tile edge.
-//   - K is walked in stages of 128 bytes, double buffered in LDS.  A stage
-//     takes one full 128-byte cache line per row, so every L2 request is a
-//     whole line.  Activations and weights go global -> LDS directly
-//     (buffer_load ... lds, 16 B per lane, no registers in between); the loads
-//     of stage i+1 are in flight while stage i is multiplied.  4-bit weights
-//     travel packed (half the bytes).
-//   - The direct loads are issued from inline assembly and waited for with an
-//     explicit s_waitcnt: the compiler would otherwise wait for all of them
-//     before every LDS read and undo the prefetch.  They are paced, one load per
-//     two MFMAs over the first half of a stage: the CU's load path takes 64 bytes
-//     per cycle, half of a stage's duration for its 64 KiB, and a wave that
-//     queues there issues no MFMA.
-//   - LDS tiles are [row][128 B] with the eight 16-byte chunks of a row XOR-ed
-//     by (row/2)%8, which makes the 16-lane groups of a ds_read_b128 hit 16
-//     different bank groups.
-//   - The weights are the MFMA row operand and the tokens the column operand,
-//     so a lane owns one token and, by permuting which weight row sits in
-//     which MFMA row, 32 consecutive output channels of it.  The epilogue
-//     scales and narrows in registers, turns each wavefront's 128 x 64 block
-//     through LDS and writes whole 128-byte lines of Y, bypassing the caches'
-//     retention (nontemporal): the operands keep the L2.
-//   - The kernel is persistent: one workgroup per CU walks a list of tiles.
-//     The first stage of the next tile is requested while the last stage of
-//     the current one is multiplied, and the epilogue (which stages through
-//     the buffer just consumed) runs while those loads are in flight.
-//   - Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; each
-//     XCD gets a contiguous run of tiles, ordered in bands of 8 token tiles,
-//     and the workgroups of an XCD take them in turn, so that its L2 sees each
-//     operand panel once.
-//
-// Integer accumulation is exact and order independent, so the result is the
-// same whatever the tiling; the 4-bit path multiplies by 16 * w (nibble left in
-// the high half of the byte) and divides the sum by 16 exactly afterwards.
-//
-// The epilogue computes fp16_rne(fma_f32(float(acc) * x_scale, w_scale, bias)): one fp32
-// rounding fewer than three separate operations, so an output can differ from the
-// separately rounded value in the last fp16 place.
-//
-// W_BITS == 16 instantiates the same kernel for fp16 operands and fp32 sums
-// (v_mfma_f32_32x32x16_f16, the same 16 bytes of K per lane and operand): the FP16 layer
-// the paper's hardware evaluation compares against (Sec. 5.3), y = fp16(sum + bias).
-#include <type_traits>
-
-#include "vq_gemm_common.h"
-#include "vq_internal.h"
+// The int8 (and packed 4-bit, and fp16 comparison) GEMM with the dequantization epilogue:
+// the 256 x 256 workgroup tile of the kernel template in vq_gemm_kernel.h, and the choice
+// between it, the 256 x 192 tile (vq_gemm_192.hip) and the small-tile kernel
+// (vq_gemm_small.hip) for a given problem.
+#include "vq_gemm_kernel.h"
 
 namespace vq {
+
 namespace {
+typedef TileShape<2, 4, 4> Tile256;  // 2 x 4 wavefronts of 128 tokens x 64 channels
 
-constexpr int kTileT = 256;                 // tokens per workgroup
-constexpr int kTileC = 256;                 // output channels per workgroup
-constexpr int kTileK = 128;                 // K bytes per stage (one cache line per row)
-constexpr int kThreads = 512;               // 8 wavefronts
-constexpr int kWaves = kThreads / 64;
-constexpr int kXStage = kTileT * kTileK;    // 32 KiB
-constexpr int kWStage = kTileC * kTileK;    // 32 KiB (16 KiB used by packed 4-bit weights)
-constexpr int kStages = 2;
-constexpr int kLdsBytes = kStages * (kXStage + kWStage);  // 128 KiB
-constexpr int kScaleBytes = 3 * 1024;       // w_scale[256] fp32 | bias[256] fp16 (+pad) | x_scale[256] fp32
-constexpr int kEpiWave = 64 * 128;          // a wavefront stages 64 tokens x 64 channels of fp16 at a time
-constexpr int kBand = 8;                    // token tiles per band in the tile order
-constexpr int kXcds = 8;
-static_assert(kWaves * kEpiWave == kXStage + kWStage, "epilogue staging is one stage buffer pair");
-
-struct GemmArgs {
-    const int8_t* xq;
-    const float* x_scale;
-    const void* w;
-    const float* w_scale;
-    const _Float16* bias;
-    _Float16* y;
-    int32_t* acc_out;
-    int M, N, K;
-    int tiles_t, tiles_c, tiles, tiles_per_xcd;
-    int slots;  // workgroups per XCD; workgroup (xcd, slot) takes tiles slot, slot + slots, ... of its XCD
-};
-
-// Where a tile sits in the output (wave-uniform).
-struct TilePos {
-    long tok0, ch0;
-    int rows_x, rows_w;  // rows of the tile that exist (the rest is clamped on load, masked on store)
-};
-// What this wave's share of a tile's loads needs: buffer descriptors and per-lane offsets.
-struct TileLoads {
-    v4i rsrc_x, rsrc_w;
-    int voff_x[4], voff_w[4];
-};
-
-// One 32 x 32 block: int8 operands (32 values of K per lane pair) into int32 sums, or,
-// for the fp16 comparison layer, fp16 operands (16 values of K) into fp32 sums.  Both take
-// 16 bytes of each operand per lane and as long to issue.
-typedef float v16f __attribute__((ext_vector_type(16)));
-template <int W_BITS>
-struct AccOf { typedef v16i type; };
-template <>
-struct AccOf<16> { typedef v16f type; };
-__device__ __forceinline__ v16i mfma_block(v4i w, v4i x, v16i c) {
-    return __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
+// How long a launch takes in units of one 256 x 256 tile on one CU: every XCD walks its
+// share of the tiles in rounds of one tile per CU, and a tile costs what it holds.
+double rounds_cost(int M, int N, int tile_c, int num_cus) {
+    const long tiles = (long)((M + 255) / 256) * ((N + tile_c - 1) / tile_c);
+    const long per_xcd = (tiles + kXcds - 1) / kXcds;
+    const int cus_per_xcd = num_cus >= kXcds ? num_cus / kXcds : 1;
+    const long rounds = (per_xcd + cus_per_xcd - 1) / cus_per_xcd;
+    return (double)rounds * tile_c / 256.0;
 }
-__device__ __forceinline__ v16f mfma_block(v4i w, v4i x, v16f c) {
-    // (a cast between vector types of one size reinterprets the bits)
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16((half8)w, (half8)x, c, 0, 0, 0);
-}
-
-// K_TAIL:  K is a multiple of 16 but not of 128 (the last stage is partly past K).
-// GENERIC: any N and an optional copy of the integer sums; stores go out element by
-//          element.  The fast variant needs N % 8 == 0 and writes whole lines.
-template <int W_BITS, bool K_TAIL, bool GENERIC>
-__global__ __launch_bounds__(kThreads, 2) void gemm_i8_dequant(const GemmArgs a) {
-    __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes + kScaleBytes];
-    // layout: [X buffer 0][X buffer 1][W buffer 0][W buffer 1][scales]; a W buffer is
-    // [256 rows][128 B] of int8 or, for 4-bit weights, [256 rows][64 B] of nibbles.
-    int8_t* const lds_x = lds;
-    int8_t* const lds_w = lds + kStages * kXStage;
-    const unsigned lds_x_addr = (unsigned)(uintptr_t)(lds_ptr)lds_x;
-    const unsigned lds_w_addr = (unsigned)(uintptr_t)(lds_ptr)lds_w;
-    int8_t* const lds_sc = lds + kLdsBytes;  // w_scale | bias | x_scale of the current tile
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Waves w and w+4 share a SIMD: they get the same token half and channel
-    // slabs two apart, so a tile that is only half full of channels still
-    // leaves one working wave on every SIMD.
-    const int wave_t = wave & 1;   // which 128 tokens
-    const int wave_c = wave >> 1;  // which 64 channels
-    // (W_BITS == 16: fp16 operands, the comparison layer; rows are 2 K bytes and everything up
-    // to the MFMA itself treats them like int8 rows of that many bytes)
-    const int K = (W_BITS == 16) ? 2 * a.K : a.K;      // bytes per activation row
-    constexpr int kWDiv = (W_BITS == 4) ? 2 : 1;        // activation bytes per weight byte
-    const int nk = (K + kTileK - 1) / kTileK;
-
-    // ---- global -> LDS mapping ---------------------------------------------
-    // One direct load fills 1 KiB; lane l writes bytes [16 l, 16 l + 16).
-    // int8 tiles: 8 rows x 128 B per load, lane l = row l/8, physical chunk l%8,
-    // which under the swizzle holds logical chunk (l%8) ^ ((row/2)%8).  Wave w
-    // loads row groups w, w+8, w+16, w+24 of each tile, so row/2 mod 8 is
-    // (4 (w%2) + l/16) % 8 for all of them.
-    // Packed 4-bit tile [256 rows][64 B]: 16 rows x 64 B per load, lane l = row l/4,
-    // physical chunk l%4 holding logical chunk (l%4) ^ ((row/4)%4) = (l%4) ^ (l/16);
-    // wave w loads row groups w and w+8.
-    auto decode_tile = [&](int idx, TilePos& t, TileLoads& ld) {
-        const int l = opaque(lane);
-        const int ld_chunk16 = ((l & 7) ^ ((4 * (wave & 1) + (l >> 4)) & 7)) << 4;
-        const int ld_chunk16_w4 = ((l & 3) ^ (l >> 4)) << 4;
-        const int logical = (blockIdx.x % kXcds) * a.tiles_per_xcd + idx;
-        const int band_tiles = kBand * a.tiles_c;
-        const int band = logical / band_tiles;
-        const int band_first = band * kBand;
-        const int band_rows = min(a.tiles_t - band_first, kBand);
-        const int in_band = logical - band * band_tiles;
-        t.tok0 = (long)(band_first + in_band % band_rows) * kTileT;
-        t.ch0 = (long)(in_band / band_rows) * kTileC;
-        t.rows_x = (int)min((long)kTileT, a.M - t.tok0);
-        t.rows_w = (int)min((long)kTileC, a.N - t.ch0);
-        ld.rsrc_x = make_rsrc(a.xq + t.tok0 * K, clamp_u32((a.M - t.tok0) * (long)K));
-        ld.rsrc_w = make_rsrc((const int8_t*)a.w + t.ch0 * (K / kWDiv),
-                              clamp_u32((a.N - t.ch0) * (long)(K / kWDiv)));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = (wave + 8 * j) * 8 + (l >> 3);
-            ld.voff_x[j] = min(r, t.rows_x - 1) * K + ld_chunk16;
-            if (W_BITS != 4) {
-                ld.voff_w[j] = min(w_row_to_channel(r), t.rows_w - 1) * K + ld_chunk16;
-            } else {
-                const int r4 = (wave + 8 * (j & 1)) * 16 + (l >> 2);
-                ld.voff_w[j] = min(w_row_to_channel(r4), t.rows_w - 1) * (K / 2) + ld_chunk16_w4;
-            }
-        }
-    };
-    auto tile_exists = [&](int idx) {
-        return idx < a.tiles_per_xcd && (int)(blockIdx.x % kXcds) * a.tiles_per_xcd + idx < a.tiles;
-    };
-
-    // One quarter of a stage's loads (this wave's share): issued between the K steps of
-    // the stage being multiplied, so that no wave sits in a queue of eight loads.
-    auto issue_part = [&](const TileLoads& ld, int buf, int k0, int j) {
-        load_stage_to_lds_16<K_TAIL>(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
-        if (W_BITS != 4)
-            load_stage_to_lds_16<K_TAIL>(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j], k0);
-        else if (j < 2)
-            load_stage_to_lds_16<K_TAIL>(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
-                           k0 / 2);
-    };
-
-    // One load of a wave's share of a stage (X and W loads alternate: s = 2 j + {0: X, 1: W}).
-    constexpr int kSingles = (W_BITS != 4) ? 8 : 6;  // packed 4-bit weights need only two W loads
-    auto issue_single = [&](const TileLoads& ld, int buf, int k0, int s) {
-        const int j = (W_BITS != 4 || s < 4) ? (s >> 1) : (s - 2);
-        const bool is_w = (W_BITS != 4 || s < 4) ? (s & 1) : false;
-        if (!is_w)
-            load_stage_to_lds_16<K_TAIL>(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
-        else
-            load_stage_to_lds_16<K_TAIL>(ld.rsrc_w, lds_w_addr + buf * kWStage + (wave + 8 * j) * 1024, ld.voff_w[j],
-                           W_BITS != 4 ? k0 : k0 / 2);
-    };
-
-    // ---- LDS -> MFMA operand mapping -----------------------------------------
-    // Operand rows of a 32x32x32 block: lane l supplies row l%32, 16 bytes of K
-    // chosen by l/32; a stage holds four such K steps (chunks 2ks and 2ks+1).
-    // The chunk index of K step ks is (2 ks + l/32) ^ swizzle = ((l/32) ^ swizzle) ^ 2 ks, so the
-    // byte offset of step ks is that of step 0 with 32 ks XOR-ed in.
-    const int fr_row = lane & 31;
-    const int x_off0 = (wave_t * 128 + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4);
-    const int w_off0 = (W_BITS != 4)
-                           ? (wave_c * 64 + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4)
-                           // 8 bytes of nibbles: 16-byte chunk ks (swizzled by (row/4)%4), half l/32
-                           : (wave_c * 64 + fr_row) * (kTileK / 2) + (((fr_row >> 2) & 3) << 4) + (lane >> 5) * 8;
-    auto x_off = [&](int ks) { return x_off0 ^ (ks << 5); };
-    auto w_off = [&](int ks) { return w_off0 ^ (ks << (W_BITS != 4 ? 5 : 4)); };
-
-    // ---- the tiles of this workgroup -------------------------------------------
-    int idx = blockIdx.x / kXcds;
-    if (!tile_exists(idx)) return;  // uniform per workgroup
-    TilePos cur;   // the tile being multiplied
-    TileLoads ld;  // the tile whose stages are being requested (the next one during the last stage)
-    decode_tile(idx, cur, ld);
-    int buf = 0;  // LDS buffer of the stage about to be multiplied
-#pragma unroll
-    for (int j = 0; j < 4; ++j) issue_part(ld, 0, 0, j);
-    wait_loads_and_barrier();  // the first tile's first stage (later ones arrive behind an epilogue)
-
-    // Invariant at the top of a stage: its operands have landed in buffer `buf` for every
-    // wave, and nobody reads or writes the other buffer any more.
-    while (true) {
-        const int next_idx = idx + a.slots;
-        const bool has_next = tile_exists(next_idx);
-        TilePos nxt = cur;
-
-        // a wave whose 64 channels (or 128 tokens) lie wholly past the matrix has nothing to multiply
-        const bool wave_live = (wave_c * 64 < cur.rows_w) && (wave_t * 128 < cur.rows_x);
-
-        // Scales and bias of the tile: threads 0..255 fetch one channel and one token each
-        // here and park them in LDS behind the last stage, where every lane of the epilogue
-        // finds them.  Entries past N or M, and a missing bias, are zero.
-        float pre_ws = 0.0f, pre_xs = 0.0f;
-        _Float16 pre_b = (_Float16)0.0f;
-        if (wave < 4) {
-            const int i = wave * 64 + opaque(lane);
-            if (cur.ch0 + i < a.N) {
-                if (W_BITS != 16) pre_ws = a.w_scale[cur.ch0 + i];
-                if (a.bias) pre_b = a.bias[cur.ch0 + i];
-            }
-            if (W_BITS != 16 && cur.tok0 + i < a.M) pre_xs = a.x_scale[cur.tok0 + i];
-        }
-
-        auto park_scales = [&]() {
-            if (wave < 4) {
-                const int i = wave * 64 + opaque(lane);
-                *(float*)(lds_sc + i * 4) = pre_ws;
-                *(_Float16*)(lds_sc + 1024 + i * 2) = pre_b;
-                *(float*)(lds_sc + 2048 + i * 4) = pre_xs;
-            }
-        };
-
-        typedef typename AccOf<W_BITS>::type acc_t;
-        acc_t acc[2][4];
-        v4i xf[2][4], wf[2][2];  // operand registers, double buffered; [1] carries K step 3 across stages
-        const acc_t kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-
-        // One stage = four K steps of 8 MFMAs per wave.  The schedule is skewed by one K step:
-        // the MFMAs of a stage's last K step are issued at the start of the next stage, behind
-        // the barrier, where they cover the latency of that stage's first LDS reads (otherwise
-        // every wave of the CU would sit idle there).  Compile-time flags: FIRST = the tile's
-        // first stage (nothing deferred to run; its first K step starts the accumulators from
-        // a constant zero), LAST = its last one (nothing is deferred past the epilogue).
-        auto stage = [&](const int it, auto first_tag, auto last_tag) __attribute__((always_inline)) {
-            constexpr bool FIRST = decltype(first_tag)::value;
-            constexpr bool LAST = decltype(last_tag)::value;
-            // what to request while this stage is multiplied: the next stage of this tile,
-            // or the first stage of the next tile
-            const bool more = it + 1 < nk;
-            const bool fetch = more || has_next;
-            if (!more && has_next) decode_tile(next_idx, nxt, ld);
-            const int fk0 = more ? (it + 1) * kTileK : 0;
-
-            const int8_t* xs = lds_x + buf * kXStage;
-            const int8_t* ws = lds_w + buf * kWStage;
-            // Operand registers are double buffered: the LDS reads of K step ks+1 are issued
-            // among the MFMAs of step ks, which cover their latency.
-            // A K step = 8 MFMAs in four pieces of two.  A piece carries at most one global load
-            // (so that a wave never sits in the load queue while the matrix pipe waits for it:
-            // the 64 loads of a stage keep the CU's address path busy for half of the stage) and
-            // two LDS reads of the step after; sched_barrier(0) keeps the pieces apart.
-            //   reads of the next step in the order of their first use: w0 x0 | x1 x2 | x3 w1
-            auto read_one = [&](int ks, int r, v4i(&xo)[4], v4i(&wo)[2]) __attribute__((always_inline)) {
-                const bool past_k = K_TAIL && it == nk - 1 && it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K;
-                if (r == 0 || r == 5) {
-                    const int cb = (r == 0) ? 0 : 1;
-                    if (W_BITS != 4)
-                        wo[cb] = *(const v4i*)(ws + w_off(ks) + cb * 32 * kTileK);
-                    else
-                        wo[cb] = widen_nibbles(*(const v2i*)(ws + w_off(ks) + cb * 32 * (kTileK / 2)));
-                    // K is a multiple of 16 but not of 128: chunks past K hold bytes of the next
-                    // row (or nothing); a zero weight operand removes them.
-                    if (past_k) wo[cb] = v4i{0, 0, 0, 0};
-                } else {
-                    const int tb = r - 1;
-                    xo[tb] = *(const v4i*)(xs + x_off(ks) + tb * 32 * kTileK);
-                }
-            };
-            auto mfma_one = [&](int idx, const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag) __attribute__((always_inline)) {
-                const int cb = idx >> 2, tb = idx & 3;
-                if constexpr (decltype(zero_tag)::value)
-                    acc[cb][tb] = mfma_block(wi[cb], xi[tb], kZero16);
-                else
-                    acc[cb][tb] = mfma_block(wi[cb], xi[tb], acc[cb][tb]);
-            };
-            // read_ks < 0: nothing left to read (the tile's last K step); first_load < 0: no loads
-            auto k_step = [&](const v4i(&xi)[4], const v4i(&wi)[2], auto zero_tag, int read_ks, v4i(&xo)[4],
-                              v4i(&wo)[2], int first_load) __attribute__((always_inline)) {
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    if (fetch && first_load >= 0 && first_load + p < kSingles)
-                        issue_single(ld, buf ^ 1, fk0, first_load + p);
-                    mfma_one(2 * p, xi, wi, zero_tag);
-                    mfma_one(2 * p + 1, xi, wi, zero_tag);
-                    if (read_ks >= 0 && p < 3) {
-                        read_one(read_ks, 2 * p, xo, wo);
-                        read_one(read_ks, 2 * p + 1, xo, wo);
-                        if (W_BITS != 4) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            };
-            constexpr std::false_type kAccumulate{};
-            if (FIRST) {
-                // nothing deferred to cover them: the first K step's operands are read up front
-#pragma unroll
-                for (int r = 0; r < 6; ++r) read_one(0, r, xf[0], wf[0]);
-                __builtin_amdgcn_sched_barrier(0);
-            } else {
-                k_step(xf[1], wf[1], kAccumulate, 0, xf[0], wf[0], 0);  // K step 3 of the previous stage
-            }
-            k_step(xf[0], wf[0], first_tag, 1, xf[1], wf[1], FIRST ? 0 : 4);  // K step 0
-            k_step(xf[1], wf[1], kAccumulate, 2, xf[0], wf[0], FIRST ? 4 : -1);  // K step 1
-            k_step(xf[0], wf[0], kAccumulate, 3, xf[1], wf[1], -1);  // K step 2
-            // K step 3 (otherwise at the start of the next stage)
-            if (LAST) k_step(xf[1], wf[1], kAccumulate, -1, xf[0], wf[0], -1);
-            if (!more) park_scales();
-            // The stage requested above has landed for every wave and every wave is done
-            // reading this one.  After the last stage this also says: the scales are in LDS,
-            // the next tile's first stage is in, and only stores can be outstanding later.
-            wait_loads_and_barrier();
-            buf ^= 1;
-        };
-        if (!wave_live) {
-            // nothing to multiply in this tile, but this wave's share of the loads is needed
-#pragma unroll 1
-            for (int it = 0; it < nk; ++it) {
-                const bool more = it + 1 < nk;
-                if (!more && has_next) decode_tile(next_idx, nxt, ld);
-                if (more || has_next) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) issue_part(ld, buf ^ 1, more ? (it + 1) * kTileK : 0, j);
-                }
-                if (!more) park_scales();
-                wait_loads_and_barrier();
-                buf ^= 1;
-            }
-        } else if (nk == 1) {
-            stage(0, std::true_type{}, std::true_type{});
-        } else {
-            stage(0, std::true_type{}, std::false_type{});
-#pragma unroll 1
-            for (int it = 1; it < nk - 1; ++it) stage(it, std::false_type{}, std::false_type{});
-            stage(nk - 1, std::false_type{}, std::true_type{});
-        }
-        // `buf` now names the buffer that holds the next tile's first stage; the other one
-        // (the last stage multiplied) becomes the epilogue's staging area.
-
-        // ---- epilogue ------------------------------------------------------------
-        // Lane (h = lane/32, t = lane%32) holds, for each of its 4 token blocks, the
-        // 32 channels chl .. chl+31: accumulator block b, register r <-> chl + 16 b + r.
-        if (wave_live) {
-            const int el = opaque(lane);  // (the epilogue's per-lane values are not kept across the mainloop)
-            const int h = el >> 5;
-            const long chw = cur.ch0 + wave_c * 64;  // first channel of this wave
-            // the 4-bit path accumulated 16 * w: fold the exact 1/16 into the channel scale
-            const float wmul = (W_BITS == 4) ? 0.0625f : 1.0f;
-            float wsc[32], bsc[32];
-            const int8_t* sc_w = lds_sc + (wave_c * 64 + 32 * h) * 4;
-            const int8_t* sc_b = lds_sc + 1024 + (wave_c * 64 + 32 * h) * 2;
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                const v4f sv = *(const v4f*)(sc_w + 16 * g);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) wsc[4 * g + e] = sv[e] * wmul;
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const half8 bv = *(const half8*)(sc_b + 16 * g);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) bsc[8 * g + e] = (float)bv[e];
-            }
-
-            // staging: [64 token rows][128 B], 16-byte chunks XOR-ed by (row/2)%8; waves
-            // 0..3 use the X buffer just consumed, waves 4..7 the W buffer.
-            // (byte offsets into `lds`; the staging areas are 8 KiB aligned, so the XORs below
-            // stay inside the chunk bits)
-            const int stage = (wave < 4 ? (buf ^ 1) * kXStage + wave * kEpiWave
-                                        : kStages * kXStage + (buf ^ 1) * kWStage + (wave - 4) * kEpiWave);
-            // writes: this lane's token row (el%32, +32 for odd tb), logical chunk 4h+g
-            const int st_wr = stage + (el & 31) * 128 + ((4 * h ^ ((el >> 1) & 7)) << 4);
-            // flush reads: row 8i + el/8, logical chunk el%8 (its XOR mask alternates with i)
-            const int st_rd = stage + (el >> 3) * 128 + (((el & 7) ^ (el >> 4)) << 4);
-            // Flush stores are range-checked buffer stores relative to the tile's first token
-            // row: rows past M fall behind the end of the buffer, lanes whose channels lie past
-            // N get an offset behind it (N < 2^21 on this path, so nothing wraps).
-            const int cl = (int)chw + (el & 7) * 8;
-            const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
-                a.y + cur.tok0 * a.N, 0, (int)clamp_u32((long)cur.rows_x * a.N * 2), kRsrcFlags);
-            const unsigned y_off0 =
-                (cl < a.N) ? (unsigned)(((wave_t * 128 + (el >> 3)) * a.N + cl) * 2) : 0x80000000u;
-#pragma unroll
-            for (int tb = 0; tb < 4; ++tb) {
-                const int tl = wave_t * 128 + tb * 32 + (el & 31);  // token within the tile
-                const float xsc = *(const float*)(lds_sc + 2048 + tl * 4);
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int b = g >> 1, r0 = (g & 1) * 8;
-                    half8 out;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        float y;
-                        if (W_BITS == 16) {  // the fp32 sum of the fp16 products, plus the bias
-                            y = (float)acc[b][tb][r0 + e] + bsc[8 * g + e];
-                        } else {
-                            const float f = (float)acc[b][tb][r0 + e] * xsc;
-                            y = __builtin_fmaf(f, wsc[8 * g + e], bsc[8 * g + e]);
-                        }
-                        // keep the fp32 result as such: the narrowing below then is a plain
-                        // round-to-nearest-even of it in every variant of this kernel (a fused
-                        // multiply-add-narrow instruction would round only once)
-                        asm("" : "+v"(y));
-                        out[e] = (_Float16)y;
-                    }
-                    if (!GENERIC) {
-                        *(half8*)(lds + (st_wr ^ (g << 4)) + (tb & 1) * 4096) = out;
-                    } else if (tl < cur.rows_x) {
-                        const long tok = cur.tok0 + tl;
-                        const long c0 = chw + 32 * h + 8 * g;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            if (c0 + e < a.N) {
-                                a.y[tok * a.N + c0 + e] = out[e];
-                                if (a.acc_out) {
-                                    const int v = (int)acc[b][tb][r0 + e];
-                                    a.acc_out[tok * a.N + c0 + e] = (W_BITS == 4) ? (v >> 4) : v;
-                                }
-                            }
-                        }
-                    }
-                }
-                if (!GENERIC && (tb & 1)) {
-                    // 64 token rows x 128 B are staged: write them out, a full line per 8 lanes.
-                    // Only this wave touches its staging area and the LDS operations of a wave
-                    // execute in order; the fences only keep the compiler from reordering them.
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    v4i rows[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        rows[i] = *(const v4i*)(lds + (st_rd ^ ((i & 1) << 6)) + i * 1024);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        __builtin_amdgcn_raw_buffer_store_b128(
-                            rows[i], rsrc_y, y_off0 + (unsigned)(((tb - 1) * 32 + i * 8) * a.N * 2), 0, 2 /* nontemporal */);
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                }
-            }
-        }
-        if (!has_next) break;
-        // every wave has left its staging area: the next tile's second stage may land there
-        wait_lds_and_barrier();
-        cur = nxt;
-        idx = next_idx;
-    }
-}
-
 }  // namespace
 
 hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, int w_bits,
                        const float* w_scale, const void* bias_f16, void* y_f16, int32_t* acc_out,
                        int M, int N, int K, int num_cus, hipStream_t stream) {
+    // A problem whose large tiles would leave more than half of the CUs idle is latency
+    // bound: the small-tile kernel puts many more loads in flight.
+    const long tiles256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+    if (tiles256 * 2 <= num_cus && w_bits != 16)
+        return launch_gemm_small(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, acc_out, M, N, K, stream);
     GemmArgs a;
     a.xq = xq;
     a.x_scale = x_scale;
@@ -516,36 +39,16 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     a.M = M;
     a.N = N;
     a.K = K;
-    a.tiles_t = (M + kTileT - 1) / kTileT;
-    a.tiles_c = (N + kTileC - 1) / kTileC;
-    const long tiles = (long)a.tiles_t * a.tiles_c;
-    if (tiles > 0x7FFFFFF0l) return hipErrorInvalidValue;
-    // A problem whose large tiles would leave more than half of the CUs idle is latency
-    // bound: the small-tile kernel puts many more loads in flight.
-    if (tiles * 2 <= num_cus && w_bits != 16)
-        return launch_gemm_small(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, acc_out, M, N, K, stream);
-    a.tiles = (int)tiles;
-    a.tiles_per_xcd = (a.tiles + kXcds - 1) / kXcds;
-    // one workgroup per CU (the kernel needs most of a CU's LDS), fewer if there are fewer tiles
-    const int cus_per_xcd = num_cus >= kXcds ? num_cus / kXcds : 1;
-    a.slots = a.tiles_per_xcd < cus_per_xcd ? a.tiles_per_xcd : cus_per_xcd;
-    const dim3 grid((unsigned)(a.slots * kXcds)), block(kThreads);
-    const bool tail = ((w_bits == 16 ? 2 * K : K) % kTileK) != 0;  // (in bytes of an activation row)
-    const bool generic = (N % 8) != 0 || acc_out != nullptr || N >= (1 << 21);
-#define VQ_LAUNCH_GEMM(BITS, TAIL, GEN) \
-    hipLaunchKernelGGL((gemm_i8_dequant<BITS, TAIL, GEN>), grid, block, 0, stream, a)
-    if (w_bits == 8) {
-        if (tail) { if (generic) VQ_LAUNCH_GEMM(8, true, true); else VQ_LAUNCH_GEMM(8, true, false); }
-        else      { if (generic) VQ_LAUNCH_GEMM(8, false, true); else VQ_LAUNCH_GEMM(8, false, false); }
-    } else if (w_bits == 16) {
-        if (tail) { if (generic) VQ_LAUNCH_GEMM(16, true, true); else VQ_LAUNCH_GEMM(16, true, false); }
-        else      { if (generic) VQ_LAUNCH_GEMM(16, false, true); else VQ_LAUNCH_GEMM(16, false, false); }
-    } else {
-        if (tail) { if (generic) VQ_LAUNCH_GEMM(4, true, true); else VQ_LAUNCH_GEMM(4, true, false); }
-        else      { if (generic) VQ_LAUNCH_GEMM(4, false, true); else VQ_LAUNCH_GEMM(4, false, false); }
-    }
-#undef VQ_LAUNCH_GEMM
-    return hipGetLastError();
+    a.tiles_t = a.tiles_c = a.tiles = a.tiles_per_xcd = a.slots = 0;  // (set for the chosen tile)
+    // The narrower tile moves a sixth more operand bytes per multiply-add: it has to save
+    // more than that in rounds (VQ_GEMM_TILE_MARGIN) to be chosen.
+#ifdef VQ_GEMM_FORCE_TILE
+    const bool narrow = VQ_GEMM_FORCE_TILE == 192;
+#else
+    const bool narrow = rounds_cost(M, N, 192, num_cus) * 1.05 < rounds_cost(M, N, 256, num_cus);
+#endif
+    if (narrow) return launch_gemm_192(a, w_bits, num_cus, stream);
+    return launch_gemm_shape<Tile256>(a, w_bits, num_cus, stream);
 }
 
 }  // namespace vq

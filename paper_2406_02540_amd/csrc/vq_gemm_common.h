@@ -43,6 +43,10 @@ __device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
     return r;
 }
 
+// (M0 is a reserved register: naming it as clobbered is what tells the compiler that these
+// statements change it, and the compiler answers with a warning that says no more than that.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 // 16 bytes per lane from buffer offset voff + soff straight into LDS at
 // lds_addr + 16 * lane (lds_addr is wave-uniform and goes through M0, which the
 // statement declares as clobbered).  Counts in vmcnt; the compiler does not know
@@ -56,6 +60,19 @@ __device__ __forceinline__ void load_to_lds_16(v4i rsrc, unsigned lds_addr, int 
         : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
         : "memory", "m0");
 }
+
+// 4 bytes per lane from buffer offset voff + soff into LDS at lds_addr + 4 * lane.
+__device__ __forceinline__ void load_to_lds_4(v4i rsrc, unsigned lds_addr, int voff, int soff) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "buffer_load_dword %1, %2, %3 offen lds"
+        :
+        : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+        : "memory", "m0");
+}
+
+#pragma clang diagnostic pop
 
 // The same for a stage at byte k0 of the rows.  K a multiple of the stage: k0 rides in the scalar
 // offset.  Otherwise (the last stage reaches past K) it is added to the per-lane offset, the part

@@ -1,0 +1,595 @@
+// int8 x int8 -> int32 MFMA GEMM with the dequantization epilogue, for gfx950: the kernel
+// template.  vq_gemm.hip and vq_gemm_192.hip instantiate it for two workgroup tiles and
+// vq_gemm.hip chooses between them.
+//
+// Computes, for tokens m and output channels n (ViDiT-Q appendix "Hardware
+// implementation of quantized linear layers"; Sec. 4.1 for the grouping):
+//     acc[m,n] = sum_k xq[m,k] * wq[n,k]
+//     y[m,n]   = fp16(float(acc) * x_scale[m] * w_scale[n] + bias[n])
+// W4A8 (appendix "Performance under lower bitwidth"): 4-bit weights are staged
+// in LDS packed and widened to int8 on their way from LDS into the MFMA operand
+// registers; the mainloop is otherwise the same.
+//
+// Shape of the kernel
+//   - workgroup tile: 256 tokens x (64 WC) output channels, WT x WC wavefronts, each
+//     wavefront (32 TB) tokens x 64 channels = 2 x TB MFMA 32x32x32 blocks.  Two tiles:
+//       256 x 256: 2 x 4 wavefronts of 128 x 64 (128 int32 accumulators per lane), two
+//                  wavefronts per SIMD;
+//       256 x 192: 4 x 3 wavefronts of 64 x 64 (64 accumulators), three per SIMD: for
+//                  channel counts that 256 does not divide well (1152 = 6 x 192: no
+//                  half-empty column of tiles, and 768 tiles of 3/4 of the work fill 256
+//                  CUs in three even rounds where 640 tiles of 256 x 256 need three
+//                  rounds of whole tiles for 2.25 rounds of work).
+//     The tile is large because the L2 -> CU path, not HBM, is what the operand traffic
+//     loads: bytes per multiply-add fall with the tile edge.
+//   - K is walked in stages of 128 bytes, double buffered in LDS.  A stage
+//     takes one full 128-byte cache line per row, so every L2 request is a
+//     whole line (with 64-byte stages the same bytes cost twice the requests and the
+//     CU's address path saturates).  Activations and weights go global -> LDS directly
+//     (buffer_load ... lds, 16 B per lane, no registers in between); the loads
+//     of stage i+1 are in flight while stage i is multiplied.  4-bit weights
+//     travel packed (half the bytes).
+//   - The direct loads are issued from inline assembly and waited for with an
+//     explicit s_waitcnt: the compiler would otherwise wait for all of them
+//     before every LDS read and undo the prefetch.  They are paced, one load per
+//     two MFMAs from the start of a stage: the CU's load path takes 64 bytes
+//     per cycle, and a wave that queues there issues no MFMA.
+//   - LDS tiles are [row][128 B] with the eight 16-byte chunks of a row XOR-ed
+//     by (row/2)%8, which makes the 16-lane groups of a ds_read_b128 hit 16
+//     different bank groups.
+//   - The weights are the MFMA row operand and the tokens the column operand,
+//     so a lane owns one token and, by permuting which weight row sits in
+//     which MFMA row, 32 consecutive output channels of it.  The epilogue
+//     scales and narrows in registers, turns each wavefront's block
+//     through LDS and writes whole 128-byte lines of Y, bypassing the caches'
+//     retention (nontemporal): the operands keep the L2.
+//   - The kernel is persistent: one workgroup per CU walks a list of tiles.
+//     The first stage of the next tile is requested while the last stage of
+//     the current one is multiplied, and the epilogue (which stages through
+//     the buffer just consumed) runs while those loads are in flight.
+//   - Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; each
+//     XCD gets a contiguous run of tiles, ordered in bands of 8 token tiles,
+//     and the workgroups of an XCD take them in turn, so that its L2 sees each
+//     operand panel once.
+//
+// Integer accumulation is exact and order independent, so the result is the
+// same whatever the tiling; the 4-bit path multiplies by 16 * w (nibble left in
+// the high half of the byte) and divides the sum by 16 exactly afterwards.
+//
+// The epilogue computes fp16_rne(fma_f32(float(acc) * x_scale, w_scale, bias)): one fp32
+// rounding fewer than three separate operations, so an output can differ from the
+// separately rounded value in the last fp16 place.
+//
+// W_BITS == 16 instantiates the same kernel for fp16 operands and fp32 sums
+// (v_mfma_f32_32x32x16_f16, the same 16 bytes of K per lane and operand): the FP16 layer
+// the paper's hardware evaluation compares against (Sec. 5.3), y = fp16(sum + bias).
+#pragma once
+#include <type_traits>
+
+#include "vq_gemm_common.h"
+#include "vq_internal.h"
+
+namespace vq {
+
+struct GemmArgs {
+    const int8_t* xq;
+    const float* x_scale;
+    const void* w;
+    const float* w_scale;
+    const _Float16* bias;
+    _Float16* y;
+    int32_t* acc_out;
+    int M, N, K;
+    int tiles_t, tiles_c, tiles, tiles_per_xcd;
+    int slots;  // workgroups per XCD; workgroup (xcd, slot) takes tiles slot, slot + slots, ... of its XCD
+};
+
+// The 256 x 192 tile (vq_gemm_192.hip); the tile fields of `a` are filled in by the callee.
+hipError_t launch_gemm_192(const GemmArgs& a, int w_bits, int num_cus, hipStream_t stream);
+
+namespace {
+
+constexpr int kTileK = 128;                 // K bytes per stage (one cache line per row)
+constexpr int kStages = 2;
+constexpr int kScaleBytes = 3 * 1024;       // w_scale[256] fp32 | bias[256] fp16 (+pad) | x_scale[256] fp32
+constexpr int kBand = 8;                    // token tiles per band in the tile order
+constexpr int kXcds = 8;
+
+// WT x WC wavefronts of (32 TB) tokens x 64 channels.
+template <int WT_, int WC_, int TB_>
+struct TileShape {
+    static constexpr int WT = WT_, WC = WC_, TB = TB_;
+    static constexpr int kWaves = WT * WC;
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kWavesPerSimd = kWaves / 4;
+    static constexpr int kTileT = WT * TB * 32;       // tokens per workgroup
+    static constexpr int kTileC = WC * 64;            // output channels per workgroup
+    static constexpr int kXStage = kTileT * kTileK;   // 32 KiB
+    static constexpr int kWStage = kTileC * kTileK;   // (half of it used by packed 4-bit weights)
+    static constexpr int kLdsBytes = kStages * (kXStage + kWStage);
+    // Global -> LDS loads of 1 KiB (8 rows of int8, 16 rows of nibbles).  The X tile is 32 of them,
+    // four for each of the first eight waves.  With eight waves every wave also takes its share
+    // of the W tile; with twelve, waves 8..11 load the W tile and nothing else.
+    static constexpr bool kSplitRoles = kWaves > 8;
+    static constexpr int kWLoaders = kSplitRoles ? kWaves - 8 : 8;
+    static constexpr int kWPer8 = kTileC / 8 / kWLoaders;    // int8 (and fp16) W loads per loading wave
+    static constexpr int kWPer4 = kTileC / 16 / kWLoaders;   // packed 4-bit W loads per loading wave
+    // Epilogue: a wave stages kFlushTb blocks of 32 tokens x 64 channels of fp16 at a time, in
+    // the stage buffers just consumed (the X buffer first, then the W buffer).
+    static constexpr int kFlushTb = (kWaves * TB * 4096 <= kXStage + kWStage) ? TB : ((kWaves * 8192 <= kXStage + kWStage) ? 2 : 1);
+    static constexpr int kEpiWave = kFlushTb * 4096;
+    static constexpr int kEpiInX = kXStage / kEpiWave;       // waves that stage in the X buffer
+    static_assert(kTileT == 256, "scales are fetched by threads 0..255, one token each");
+    static_assert(kTileC <= 256 && kWaves % 4 == 0 && kWaves >= 8, "tile shape");
+    static_assert(kTileC / 8 % kWLoaders == 0 && kTileC / 16 % kWLoaders == 0, "W loads divide evenly");
+    static_assert((kWaves - kEpiInX) * kEpiWave <= kWStage || kWaves <= kEpiInX, "staging fits the consumed buffers");
+    static_assert(TB % kFlushTb == 0, "whole flushes");
+};
+
+// Where a tile sits in the output (wave-uniform).
+struct TilePos {
+    long tok0, ch0;
+    int rows_x, rows_w;  // rows of the tile that exist (the rest is clamped on load, masked on store)
+};
+// What this wave's share of a tile's loads needs: buffer descriptors and per-lane offsets.
+struct TileLoads {
+    v4i rsrc_x, rsrc_w;
+    int voff_x[4], voff_w[6];
+};
+
+// One 32 x 32 block: int8 operands (32 values of K per lane pair) into int32 sums, or,
+// for the fp16 comparison layer, fp16 operands (16 values of K) into fp32 sums.  Both take
+// 16 bytes of each operand per lane and as long to issue.
+typedef float v16f __attribute__((ext_vector_type(16)));
+template <int W_BITS>
+struct AccOf { typedef v16i type; };
+template <>
+struct AccOf<16> { typedef v16f type; };
+__device__ __forceinline__ v16i mfma_block(v4i w, v4i x, v16i c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
+}
+__device__ __forceinline__ v16f mfma_block(v4i w, v4i x, v16f c) {
+    // (a cast between vector types of one size reinterprets the bits)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16((half8)w, (half8)x, c, 0, 0, 0);
+}
+
+// K_TAIL:  K is a multiple of 16 but not of 128 (the last stage is partly past K).
+// GENERIC: any N and an optional copy of the integer sums; stores go out element by
+//          element.  The fast variant needs N % 8 == 0 and writes whole lines.
+template <class S, int W_BITS, bool K_TAIL, bool GENERIC>
+__global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant(const GemmArgs a) {
+    constexpr int TB = S::TB;
+    constexpr int kXStage = S::kXStage, kWStage = S::kWStage, kLdsBytes = S::kLdsBytes;
+    __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes + kScaleBytes];
+    // layout: [X buffer 0][X buffer 1][W buffer 0][W buffer 1][scales]; a W buffer is
+    // [rows][128 B] of int8 or, for 4-bit weights, [rows][64 B] of nibbles.
+    int8_t* const lds_x = lds;
+    int8_t* const lds_w = lds + kStages * kXStage;
+    const unsigned lds_x_addr = (unsigned)(uintptr_t)(lds_ptr)lds_x;
+    const unsigned lds_w_addr = (unsigned)(uintptr_t)(lds_ptr)lds_w;
+    int8_t* const lds_sc = lds + kLdsBytes;  // w_scale | bias | x_scale of the current tile
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Waves w, w+4 (and w+8) share a SIMD: they get the same token part and different
+    // channel slabs, so a tile that is only partly full of channels still
+    // leaves a working wave on every SIMD.
+    const int wave_t = wave % S::WT;   // which 32 TB tokens
+    const int wave_c = wave / S::WT;   // which 64 channels
+    // (W_BITS == 16: fp16 operands, the comparison layer; rows are 2 K bytes and everything up
+    // to the MFMA itself treats them like int8 rows of that many bytes)
+    const int K = (W_BITS == 16) ? 2 * a.K : a.K;      // bytes per activation row
+    constexpr int kWDiv = (W_BITS == 4) ? 2 : 1;        // activation bytes per weight byte
+    const int nk = (K + kTileK - 1) / kTileK;
+
+    // What this wave loads per stage.
+    constexpr int kWPer = (W_BITS != 4) ? S::kWPer8 : S::kWPer4;
+    const bool loads_x = !S::kSplitRoles || wave < 8;
+    const bool loads_w = !S::kSplitRoles || wave >= 8;
+    const int w_loader = S::kSplitRoles ? wave - 8 : wave;
+    const int n_singles = S::kSplitRoles ? (wave < 8 ? 4 : kWPer) : 4 + kWPer;
+
+    // ---- global -> LDS mapping ---------------------------------------------
+    // One direct load fills 1 KiB; lane l writes bytes [16 l, 16 l + 16).
+    // int8 tiles: 8 rows x 128 B per load, lane l = row l/8, physical chunk l%8,
+    // which under the swizzle holds logical chunk (l%8) ^ ((row/2)%8).  A wave's row
+    // groups g all have the parity of the wave's number, so row/2 mod 8 is
+    // (4 (g%2) + l/16) % 8 for all of them.
+    // Packed 4-bit tile [rows][64 B]: 16 rows x 64 B per load, lane l = row l/4,
+    // physical chunk l%4 holding logical chunk (l%4) ^ ((row/4)%4) = (l%4) ^ (l/16).
+    auto decode_tile = [&](int idx, TilePos& t, TileLoads& ld) {
+        const int l = opaque(lane);
+        const int logical = (blockIdx.x % kXcds) * a.tiles_per_xcd + idx;
+        const int band_tiles = kBand * a.tiles_c;
+        const int band = logical / band_tiles;
+        const int band_first = band * kBand;
+        const int band_rows = min(a.tiles_t - band_first, kBand);
+        const int in_band = logical - band * band_tiles;
+        t.tok0 = (long)(band_first + in_band % band_rows) * S::kTileT;
+        t.ch0 = (long)(in_band / band_rows) * S::kTileC;
+        t.rows_x = (int)min((long)S::kTileT, a.M - t.tok0);
+        t.rows_w = (int)min((long)S::kTileC, a.N - t.ch0);
+        ld.rsrc_x = make_rsrc(a.xq + t.tok0 * K, clamp_u32((a.M - t.tok0) * (long)K));
+        ld.rsrc_w = make_rsrc((const int8_t*)a.w + t.ch0 * (K / kWDiv),
+                              clamp_u32((a.N - t.ch0) * (long)(K / kWDiv)));
+        if (loads_x) {
+            const int ld_chunk16 = ((l & 7) ^ ((4 * (wave & 1) + (l >> 4)) & 7)) << 4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = (wave + 8 * j) * 8 + (l >> 3);
+                ld.voff_x[j] = min(r, t.rows_x - 1) * K + ld_chunk16;
+            }
+        }
+        if (loads_w) {
+            const int ld_chunk16 = ((l & 7) ^ ((4 * (w_loader & 1) + (l >> 4)) & 7)) << 4;
+            const int ld_chunk16_w4 = ((l & 3) ^ (l >> 4)) << 4;
+#pragma unroll
+            for (int j = 0; j < kWPer; ++j) {
+                const int g = w_loader + S::kWLoaders * j;   // row group of this load
+                if (W_BITS != 4)
+                    ld.voff_w[j] = min(w_row_to_channel(g * 8 + (l >> 3)), t.rows_w - 1) * K + ld_chunk16;
+                else
+                    ld.voff_w[j] = min(w_row_to_channel(g * 16 + (l >> 2)), t.rows_w - 1) * (K / 2) + ld_chunk16_w4;
+            }
+        }
+    };
+    auto tile_exists = [&](int idx) {
+        return idx < a.tiles_per_xcd && (int)(blockIdx.x % kXcds) * a.tiles_per_xcd + idx < a.tiles;
+    };
+
+    // One load of a wave's share of a stage.  A wave with both kinds alternates them (X, W, X,
+    // W, ...) as long as it has W loads left.
+    auto issue_x = [&](const TileLoads& ld, int buf, int k0, int j) {
+        load_stage_to_lds_16<K_TAIL>(ld.rsrc_x, lds_x_addr + buf * kXStage + (wave + 8 * j) * 1024, ld.voff_x[j], k0);
+    };
+    auto issue_w = [&](const TileLoads& ld, int buf, int k0, int j) {
+        load_stage_to_lds_16<K_TAIL>(ld.rsrc_w, lds_w_addr + buf * kWStage + (w_loader + S::kWLoaders * j) * 1024,
+                                     ld.voff_w[j], W_BITS != 4 ? k0 : k0 / 2);
+    };
+    auto issue_single = [&](const TileLoads& ld, int buf, int k0, int s) {
+        if (S::kSplitRoles) {
+            // (s is a compile-time constant at every call; the role is wave-uniform)
+            if (wave < 8) { if (s < 4) issue_x(ld, buf, k0, s); }
+            else          { if (s < kWPer) issue_w(ld, buf, k0, s); }
+        } else if (s < 2 * kWPer) {
+            if (s & 1) issue_w(ld, buf, k0, s >> 1); else issue_x(ld, buf, k0, s >> 1);
+        } else {
+            issue_x(ld, buf, k0, s - kWPer);
+        }
+    };
+    constexpr int kMaxSingles = S::kSplitRoles ? (kWPer > 4 ? kWPer : 4) : 4 + kWPer;
+    auto issue_all = [&](const TileLoads& ld, int buf, int k0) {
+#pragma unroll
+        for (int s = 0; s < kMaxSingles; ++s)
+            if (s < n_singles) issue_single(ld, buf, k0, s);
+    };
+
+    // ---- LDS -> MFMA operand mapping -----------------------------------------
+    // Operand rows of a 32x32x32 block: lane l supplies row l%32, 16 bytes of K
+    // chosen by l/32; a stage holds four such K steps (chunks 2ks and 2ks+1).
+    // The chunk index of K step ks is (2 ks + l/32) ^ swizzle = ((l/32) ^ swizzle) ^ 2 ks, so the
+    // byte offset of step ks is that of step 0 with 32 ks XOR-ed in.
+    const int fr_row = lane & 31;
+    const int x_off0 = (wave_t * 32 * TB + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4);
+    const int w_off0 = (W_BITS != 4)
+                           ? (wave_c * 64 + fr_row) * kTileK + (((lane >> 5) ^ ((fr_row >> 1) & 7)) << 4)
+                           // 8 bytes of nibbles: 16-byte chunk ks (swizzled by (row/4)%4), half l/32
+                           : (wave_c * 64 + fr_row) * (kTileK / 2) + (((fr_row >> 2) & 3) << 4) + (lane >> 5) * 8;
+    auto x_off = [&](int ks) { return x_off0 ^ (ks << 5); };
+    auto w_off = [&](int ks) { return w_off0 ^ (ks << (W_BITS != 4 ? 5 : 4)); };
+
+    // ---- the tiles of this workgroup -------------------------------------------
+    int idx = blockIdx.x / kXcds;
+    if (!tile_exists(idx)) return;  // uniform per workgroup
+    TilePos cur;   // the tile being multiplied
+    TileLoads ld;  // the tile whose stages are being requested (the next one during the last stage)
+    decode_tile(idx, cur, ld);
+    int buf = 0;  // LDS buffer of the stage about to be multiplied
+    issue_all(ld, 0, 0);
+    wait_loads_and_barrier();  // the first tile's first stage (later ones arrive behind an epilogue)
+
+    // Invariant at the top of a stage: its operands have landed in buffer `buf` for every
+    // wave, and nobody reads or writes the other buffer any more.
+    while (true) {
+        const int next_idx = idx + a.slots;
+        const bool has_next = tile_exists(next_idx);
+        TilePos nxt = cur;
+
+        // a wave whose 64 channels (or tokens) lie wholly past the matrix has nothing to multiply
+        const bool wave_live = (wave_c * 64 < cur.rows_w) && (wave_t * 32 * TB < cur.rows_x);
+
+        // Scales and bias of the tile: threads 0..255 fetch one channel and one token each
+        // here and park them in LDS behind the last stage, where every lane of the epilogue
+        // finds them.  Entries past N or M, and a missing bias, are zero.
+        float pre_ws = 0.0f, pre_xs = 0.0f;
+        _Float16 pre_b = (_Float16)0.0f;
+        if (wave < 4) {
+            const int i = wave * 64 + opaque(lane);
+            if (i < S::kTileC && cur.ch0 + i < a.N) {
+                if (W_BITS != 16) pre_ws = a.w_scale[cur.ch0 + i];
+                if (a.bias) pre_b = a.bias[cur.ch0 + i];
+            }
+            if (W_BITS != 16 && cur.tok0 + i < a.M) pre_xs = a.x_scale[cur.tok0 + i];
+        }
+
+        auto park_scales = [&]() {
+            if (wave < 4) {
+                const int i = wave * 64 + opaque(lane);
+                *(float*)(lds_sc + i * 4) = pre_ws;
+                *(_Float16*)(lds_sc + 1024 + i * 2) = pre_b;
+                *(float*)(lds_sc + 2048 + i * 4) = pre_xs;
+            }
+        };
+
+        typedef typename AccOf<W_BITS>::type acc_t;
+        acc_t acc[2][TB];
+        v4i xf[2][TB], wf[2][2];  // operand registers, double buffered; [1] carries K step 3 across stages
+        const acc_t kZero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+        // One stage = four K steps of 2 TB MFMAs per wave.  The schedule is skewed by one K step:
+        // the MFMAs of a stage's last K step are issued at the start of the next stage, behind
+        // the barrier, where they cover the latency of that stage's first LDS reads (otherwise
+        // every wave of the CU would sit idle there).  Compile-time flags: FIRST = the tile's
+        // first stage (nothing deferred to run; its first K step starts the accumulators from
+        // a constant zero), LAST = its last one (nothing is deferred past the epilogue).
+        auto stage = [&](const int it, auto first_tag, auto last_tag) __attribute__((always_inline)) {
+            constexpr bool FIRST = decltype(first_tag)::value;
+            constexpr bool LAST = decltype(last_tag)::value;
+            // what to request while this stage is multiplied: the next stage of this tile,
+            // or the first stage of the next tile
+            const bool more = it + 1 < nk;
+            const bool fetch = more || has_next;
+            if (!more && has_next) decode_tile(next_idx, nxt, ld);
+            const int fk0 = more ? (it + 1) * kTileK : 0;
+
+            const int8_t* xs = lds_x + buf * kXStage;
+            const int8_t* ws = lds_w + buf * kWStage;
+            // Operand registers are double buffered: the LDS reads of K step ks+1 are issued
+            // among the MFMAs of step ks, which cover their latency.
+            // A K step = 2 TB MFMAs in TB pieces of two.  A piece carries at most one global load
+            // (so that a wave never sits in the load queue while the matrix pipe waits for it)
+            // and its share of the LDS reads of the step after; sched_barrier(0) keeps the pieces
+            // apart.  Reads of the next step in the order of their first use: w0 x0 x1 .. w1
+            // (128-token waves: w0 x0 | x1 x2 | x3 w1; 64-token waves: w0 x0 x1 w1 in the first piece).
+            constexpr int kReads = TB + 2;
+            constexpr int kReadsPerPiece = (kReads + TB - 2) / (TB - 1);   // spread over all pieces but the last
+            auto read_one = [&](int ks, int r, v4i(&xo)[TB], v4i(&wo)[2]) __attribute__((always_inline)) {
+                const bool past_k = K_TAIL && it == nk - 1 && it * kTileK + (2 * ks + (lane >> 5)) * 16 >= K;
+                if (r == 0 || r == kReads - 1) {
+                    const int cb = (r == 0) ? 0 : 1;
+                    if (W_BITS != 4)
+                        wo[cb] = *(const v4i*)(ws + w_off(ks) + cb * 32 * kTileK);
+                    else
+                        wo[cb] = widen_nibbles(*(const v2i*)(ws + w_off(ks) + cb * 32 * (kTileK / 2)));
+                    // K is a multiple of 16 but not of 128: chunks past K hold bytes of the next
+                    // row (or nothing); a zero weight operand removes them.
+                    if (past_k) wo[cb] = v4i{0, 0, 0, 0};
+                } else {
+                    const int tb = r - 1;
+                    xo[tb] = *(const v4i*)(xs + x_off(ks) + tb * 32 * kTileK);
+                }
+            };
+            auto mfma_one = [&](int i, const v4i(&xi)[TB], const v4i(&wi)[2], auto zero_tag) __attribute__((always_inline)) {
+                const int cb = i / TB, tb = i % TB;
+                if constexpr (decltype(zero_tag)::value)
+                    acc[cb][tb] = mfma_block(wi[cb], xi[tb], kZero16);
+                else
+                    acc[cb][tb] = mfma_block(wi[cb], xi[tb], acc[cb][tb]);
+            };
+            // read_ks < 0: nothing left to read (the tile's last K step); first_load < 0: no loads
+            auto k_step = [&](const v4i(&xi)[TB], const v4i(&wi)[2], auto zero_tag, int read_ks, v4i(&xo)[TB],
+                              v4i(&wo)[2], int first_load) __attribute__((always_inline)) {
+#pragma unroll
+                for (int p = 0; p < TB; ++p) {
+                    if (fetch && first_load >= 0 && first_load + p < kMaxSingles && first_load + p < n_singles)
+                        issue_single(ld, buf ^ 1, fk0, first_load + p);
+                    mfma_one(2 * p, xi, wi, zero_tag);
+                    mfma_one(2 * p + 1, xi, wi, zero_tag);
+                    if (read_ks >= 0) {
+#pragma unroll
+                        for (int r = p * kReadsPerPiece; r < (p + 1) * kReadsPerPiece && r < kReads; ++r)
+                            read_one(read_ks, r, xo, wo);
+                        if (W_BITS != 4 && p * kReadsPerPiece < kReads) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // one MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, kReadsPerPiece / 2, 0);  // LDS reads
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x100, kReadsPerPiece / 2, 0);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            constexpr std::false_type kAccumulate{};
+            // K steps in the order they are issued; the e-th one of a stage carries the loads
+            // e TB .. e TB + TB - 1 of this wave's share.
+            if (FIRST) {
+                // nothing deferred to cover them: the first K step's operands are read up front
+#pragma unroll
+                for (int r = 0; r < kReads; ++r) read_one(0, r, xf[0], wf[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                k_step(xf[0], wf[0], first_tag, 1, xf[1], wf[1], 0);          // K step 0
+                k_step(xf[1], wf[1], kAccumulate, 2, xf[0], wf[0], TB);      // K step 1
+                k_step(xf[0], wf[0], kAccumulate, 3, xf[1], wf[1], 2 * TB);  // K step 2
+            } else {
+                k_step(xf[1], wf[1], kAccumulate, 0, xf[0], wf[0], 0);       // K step 3 of the previous stage
+                k_step(xf[0], wf[0], kAccumulate, 1, xf[1], wf[1], TB);      // K step 0
+                k_step(xf[1], wf[1], kAccumulate, 2, xf[0], wf[0], 2 * TB);  // K step 1
+                k_step(xf[0], wf[0], kAccumulate, 3, xf[1], wf[1], 3 * TB);  // K step 2
+            }
+            // K step 3 (otherwise at the start of the next stage)
+            if (LAST) k_step(xf[1], wf[1], kAccumulate, -1, xf[0], wf[0], -1);
+            if (!more) park_scales();
+            // The stage requested above has landed for every wave and every wave is done
+            // reading this one.  After the last stage this also says: the scales are in LDS,
+            // the next tile's first stage is in, and only stores can be outstanding later.
+            wait_loads_and_barrier();
+            buf ^= 1;
+        };
+        if (!wave_live) {
+            // nothing to multiply in this tile, but this wave's share of the loads is needed
+#pragma unroll 1
+            for (int it = 0; it < nk; ++it) {
+                const bool more = it + 1 < nk;
+                if (!more && has_next) decode_tile(next_idx, nxt, ld);
+                if (more || has_next) issue_all(ld, buf ^ 1, more ? (it + 1) * kTileK : 0);
+                if (!more) park_scales();
+                wait_loads_and_barrier();
+                buf ^= 1;
+            }
+        } else if (nk == 1) {
+            stage(0, std::true_type{}, std::true_type{});
+        } else {
+            stage(0, std::true_type{}, std::false_type{});
+#pragma unroll 1
+            for (int it = 1; it < nk - 1; ++it) stage(it, std::false_type{}, std::false_type{});
+            stage(nk - 1, std::false_type{}, std::true_type{});
+        }
+        // `buf` now names the buffer that holds the next tile's first stage; the other one
+        // (the last stage multiplied) becomes the epilogue's staging area.
+
+        // ---- epilogue ------------------------------------------------------------
+        // Lane (h = lane/32, t = lane%32) holds, for each of its TB token blocks, the
+        // 32 channels chl .. chl+31: accumulator block b, register r <-> chl + 16 b + r.
+        if (wave_live) {
+            const int el = opaque(lane);  // (the epilogue's per-lane values are not kept across the mainloop)
+            const int h = el >> 5;
+            const long chw = cur.ch0 + wave_c * 64;  // first channel of this wave
+            // the 4-bit path accumulated 16 * w: fold the exact 1/16 into the channel scale
+            const float wmul = (W_BITS == 4) ? 0.0625f : 1.0f;
+            float wsc[32], bsc[32];
+            const int8_t* sc_w = lds_sc + (wave_c * 64 + 32 * h) * 4;
+            const int8_t* sc_b = lds_sc + 1024 + (wave_c * 64 + 32 * h) * 2;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const v4f sv = *(const v4f*)(sc_w + 16 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) wsc[4 * g + e] = sv[e] * wmul;
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const half8 bv = *(const half8*)(sc_b + 16 * g);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bsc[8 * g + e] = (float)bv[e];
+            }
+
+            // staging: [32 kFlushTb token rows][128 B], 16-byte chunks XOR-ed by (row/2)%8; the first
+            // waves use the X buffer just consumed, the others the W buffer.
+            // (byte offsets into `lds`; the staging areas are 4 KiB aligned, so the XORs below
+            // stay inside the chunk bits)
+            constexpr int kFlushTb = S::kFlushTb;
+            const int stg = (wave < S::kEpiInX ? (buf ^ 1) * kXStage + wave * S::kEpiWave
+                                               : kStages * kXStage + (buf ^ 1) * kWStage + (wave - S::kEpiInX) * S::kEpiWave);
+            // writes: this lane's token row (el%32 of its block), logical chunk 4h+g
+            const int st_wr = stg + (el & 31) * 128 + ((4 * h ^ ((el >> 1) & 7)) << 4);
+            // flush reads: row 8i + el/8, logical chunk el%8 (its XOR mask alternates with i)
+            const int st_rd = stg + (el >> 3) * 128 + (((el & 7) ^ (el >> 4)) << 4);
+            // Flush stores are range-checked buffer stores relative to the tile's first token
+            // row: rows past M fall behind the end of the buffer, lanes whose channels lie past
+            // N get an offset behind it (N < 2^21 on this path, so nothing wraps).
+            const int cl = (int)chw + (el & 7) * 8;
+            const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
+                a.y + cur.tok0 * a.N, 0, (int)clamp_u32((long)cur.rows_x * a.N * 2), kRsrcFlags);
+            const unsigned y_off0 =
+                (cl < a.N) ? (unsigned)(((wave_t * 32 * TB + (el >> 3)) * a.N + cl) * 2) : 0x80000000u;
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const int tl = wave_t * 32 * TB + tb * 32 + (el & 31);  // token within the tile
+                const float xsc = *(const float*)(lds_sc + 2048 + tl * 4);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int b = g >> 1, r0 = (g & 1) * 8;
+                    half8 out;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        float y;
+                        if (W_BITS == 16) {  // the fp32 sum of the fp16 products, plus the bias
+                            y = (float)acc[b][tb][r0 + e] + bsc[8 * g + e];
+                        } else {
+                            const float f = (float)acc[b][tb][r0 + e] * xsc;
+                            y = __builtin_fmaf(f, wsc[8 * g + e], bsc[8 * g + e]);
+                        }
+                        // keep the fp32 result as such: the narrowing below then is a plain
+                        // round-to-nearest-even of it in every variant of this kernel (a fused
+                        // multiply-add-narrow instruction would round only once)
+                        asm("" : "+v"(y));
+                        out[e] = (_Float16)y;
+                    }
+                    if (!GENERIC) {
+                        *(half8*)(lds + (st_wr ^ (g << 4)) + (tb % kFlushTb) * 4096) = out;
+                    } else if (tl < cur.rows_x) {
+                        const long tok = cur.tok0 + tl;
+                        const long c0 = chw + 32 * h + 8 * g;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            if (c0 + e < a.N) {
+                                a.y[tok * a.N + c0 + e] = out[e];
+                                if (a.acc_out) {
+                                    const int v = (int)acc[b][tb][r0 + e];
+                                    a.acc_out[tok * a.N + c0 + e] = (W_BITS == 4) ? (v >> 4) : v;
+                                }
+                            }
+                        }
+                    }
+                }
+                if (!GENERIC && (tb % kFlushTb) == kFlushTb - 1) {
+                    // 32 kFlushTb token rows x 128 B are staged: write them out, a full line per 8 lanes.
+                    // Only this wave touches its staging area and the LDS operations of a wave
+                    // execute in order; the fences only keep the compiler from reordering them.
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    v4i rows[4 * kFlushTb];
+#pragma unroll
+                    for (int i = 0; i < 4 * kFlushTb; ++i)
+                        rows[i] = *(const v4i*)(lds + (st_rd ^ ((i & 1) << 6)) + i * 1024);
+#pragma unroll
+                    for (int i = 0; i < 4 * kFlushTb; ++i)
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            rows[i], rsrc_y,
+                            y_off0 + (unsigned)(((tb - (kFlushTb - 1)) * 32 + i * 8) * a.N * 2), 0, 2 /* nontemporal */);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+        if (!has_next) break;
+        // every wave has left its staging area: the next tile's second stage may land there
+        wait_lds_and_barrier();
+        cur = nxt;
+        idx = next_idx;
+    }
+}
+
+// Enqueues the kernel for tile shape S; `a` holds the operands and sizes.
+template <class S>
+hipError_t launch_gemm_shape(GemmArgs a, int w_bits, int num_cus, hipStream_t stream) {
+    a.tiles_t = (a.M + S::kTileT - 1) / S::kTileT;
+    a.tiles_c = (a.N + S::kTileC - 1) / S::kTileC;
+    const long tiles = (long)a.tiles_t * a.tiles_c;
+    if (tiles > 0x7FFFFFF0l) return hipErrorInvalidValue;
+    a.tiles = (int)tiles;
+    a.tiles_per_xcd = (a.tiles + kXcds - 1) / kXcds;
+    // one workgroup per CU (the kernel needs most of a CU's LDS), fewer if there are fewer tiles
+    const int cus_per_xcd = num_cus >= kXcds ? num_cus / kXcds : 1;
+    a.slots = a.tiles_per_xcd < cus_per_xcd ? a.tiles_per_xcd : cus_per_xcd;
+    const dim3 grid((unsigned)(a.slots * kXcds)), block(S::kThreads);
+    const bool tail = ((w_bits == 16 ? 2 * a.K : a.K) % kTileK) != 0;  // (in bytes of an activation row)
+    const bool generic = (a.N % 8) != 0 || a.acc_out != nullptr || a.N >= (1 << 21);
+#define VQ_LAUNCH_GEMM(BITS, TAIL, GEN) \
+    hipLaunchKernelGGL((gemm_i8_dequant<S, BITS, TAIL, GEN>), grid, block, 0, stream, a)
+    if (w_bits == 8) {
+        if (tail) { if (generic) VQ_LAUNCH_GEMM(8, true, true); else VQ_LAUNCH_GEMM(8, true, false); }
+        else      { if (generic) VQ_LAUNCH_GEMM(8, false, true); else VQ_LAUNCH_GEMM(8, false, false); }
+    } else if (w_bits == 16) {
+        if (tail) { if (generic) VQ_LAUNCH_GEMM(16, true, true); else VQ_LAUNCH_GEMM(16, true, false); }
+        else      { if (generic) VQ_LAUNCH_GEMM(16, false, true); else VQ_LAUNCH_GEMM(16, false, false); }
+    } else {
+        if (tail) { if (generic) VQ_LAUNCH_GEMM(4, true, true); else VQ_LAUNCH_GEMM(4, true, false); }
+        else      { if (generic) VQ_LAUNCH_GEMM(4, false, true); else VQ_LAUNCH_GEMM(4, false, false); }
+    }
+#undef VQ_LAUNCH_GEMM
+    return hipGetLastError();
+}
+
+}  // namespace
+}  // namespace vq

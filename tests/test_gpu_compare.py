@@ -45,7 +45,8 @@ def assert_f16_gemm_close(got, ref, x, w, K, b=None):
     outputs end up more than one step apart depends on how strongly the products of an output cancel, so no
     count of such outputs is asserted: the bound above is per element and complete."""
     s_abs = np.abs(x.astype(np.float64)) @ np.abs(w.astype(np.float64)).T
-    step = lambda a: np.abs(np.spacing(a.astype(np.float16))).astype(np.float64)  # noqa: E731
+    # the step of a value towards larger magnitudes: at a power of two it is the larger of the two steps next to it
+    step = lambda a: np.spacing(np.abs(a.astype(np.float16))).astype(np.float64)  # noqa: E731
     if b is not None:
         s_abs = s_abs + np.abs(b.astype(np.float64))[None, :]
     bound = 0.5 * step(got) + 0.5 * step(ref) + K * 2.0 ** -24 * s_abs

@@ -134,10 +134,14 @@ def _gemm_case(vq, oracle, M, N, K, bits, seed, bias=True, full_range=True):
     return worst, np.array_equal(host(y).view(np.uint16), y_ref.view(np.uint16))
 
 
-# The library picks its small-tile kernel when the 256 x 256 tiles would fill less than half of
-# the CUs and the persistent large-tile kernel otherwise; the last shapes are large enough for
-# the latter (>= 129 tiles on a 256-CU part) and ragged in M, N (also N % 8 != 0) and K.
-GEMM_SHAPES = [(2891, 2824, 144), (2891, 2820, 208), (2600, 3080, 128), (4099, 2056, 48), (1, 8, 16), (1, 8, 32), (33, 24, 96), (64, 128, 64), (256, 128, 128), (256, 1152, 1152),
+# The library picks its small-tile kernel when 256 x 256 tiles would fill less than half of
+# the CUs and a persistent large-tile kernel otherwise (>= 129 such tiles on a 256-CU part): the
+# 256 x 192 tile where that saves rounds of tiles (the first four shapes), else the 256 x 256 one
+# (the next three: two rounds of 256 x 256 against three of 256 x 192).  Both sets are ragged in
+# M, N (also N % 8 != 0) and K.
+GEMM_SHAPES = [(2891, 2824, 144), (2891, 2820, 208), (2600, 3080, 128), (4099, 2056, 48),
+               (5003, 5000, 144), (5003, 4996, 80), (4900, 5112, 128),
+               (1, 8, 16), (1, 8, 32), (33, 24, 96), (64, 128, 64), (256, 128, 128), (256, 1152, 1152),
                (300, 136, 224), (257, 264, 160), (513, 260, 64), (17, 7, 32), (240, 2304, 4096),
                (700, 392, 1184), (31, 129, 4608)]
 
@@ -190,16 +194,18 @@ def test_identity_weights_select_the_activations(vq):
     assert np.array_equal(host(y).astype(np.int32), xq.astype(np.int32))  # |values| < 2048: exact in fp16
 
 
-@pytest.mark.parametrize("bits,K", [(8, 4608), (4, 4608), (8, 1168), (4, 1184)])
-def test_line_store_variant_shows_its_integer_sums(vq, oracle, bits, K):
-    """The kernel variant the benchmark times (no copy of the sums, whole-line stores, and, at
-    these sizes, the persistent large-tile kernel: 12 x 12 tiles) against the oracle's integer
-    sums without the element-store variant in between: activations sparse in {-1, 0, 1} keep
-    every sum below 2048 in magnitude, so with unit scales and no bias the fp16 output IS the
-    integer sum (appendix "Hardware implementation of quantized linear layers": integer sum
-    first, scales afterwards).  K = 4608 is a whole number of K stages, the other K is not."""
-    say(f"gemm w{bits}a8 line-store variant, exact integers, K={K}")
-    M, N = 2900, 2824
+@pytest.mark.parametrize("bits,K,M,N", [(8, 4608, 2900, 2824), (4, 4608, 2900, 2824), (8, 1168, 2900, 2824),
+                                        (4, 1184, 2900, 2824), (8, 1152, 5003, 5000), (4, 1152, 5003, 5000),
+                                        (8, 1168, 5003, 5000)])
+def test_line_store_variant_shows_its_integer_sums(vq, oracle, bits, K, M, N):
+    """The kernel variants the benchmark times (no copy of the sums, whole-line stores, the
+    persistent large-tile kernels: 2900 x 2824 takes the 256 x 192 tile, 5003 x 5000 the
+    256 x 256 one) against the oracle's integer sums without the element-store variant in
+    between: activations sparse in {-1, 0, 1} keep every sum below 2048 in magnitude, so with
+    unit scales and no bias the fp16 output IS the integer sum (appendix "Hardware implementation
+    of quantized linear layers": integer sum first, scales afterwards).  K = 4608 and 1152 are a
+    whole number of K stages, the other K are not."""
+    say(f"gemm w{bits}a8 line-store variant, exact integers, M={M} N={N} K={K}")
     g = np.random.default_rng(4100 + bits + K)
     qmax = 127 if bits == 8 else 7
     nnz = 2047 // qmax if bits == 8 else 250          # |sum| <= nnz * qmax < 2048
