@@ -13,9 +13,12 @@ Prints ONE JSON line on stdout; a per-layer table goes to stderr.
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -28,6 +31,62 @@ HBM_PEAK_GBS = 8000.0
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def csrc_hash():
+    """Identifies the kernel sources a counter summary under profiles/ was taken with."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2406_02540_amd", "csrc")
+    for f in sorted(glob.glob(os.path.join(d, "*.hip")) + glob.glob(os.path.join(d, "*.h"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+class DeviceState:
+    """Samples the GPU's core clock and socket power (amdsmi) from a host thread while a loop of steps keeps the
+    device busy.  The readings are the driver's running averages, so the loop has to last about a second."""
+
+    def __init__(self):
+        self.samples, self.limit_w, self._stop, self._thread, self._h = [], None, False, None, None
+        try:
+            import amdsmi
+            self._smi = amdsmi
+            amdsmi.amdsmi_init()
+            self._h = amdsmi.amdsmi_get_processor_handles()[0]
+        except Exception as e:  # not readable here: the fields stay null
+            self._why = repr(e)[:100]
+
+    def _poll(self):
+        while not self._stop:
+            try:
+                c = self._smi.amdsmi_get_clock_info(self._h, self._smi.AmdSmiClkType.GFX)
+                p = self._smi.amdsmi_get_power_info(self._h)
+                self.samples.append((time.perf_counter(), float(c["clk"]), float(p["current_socket_power"])))
+                self.limit_w = float(p["power_limit"]) / 1e6
+            except Exception:
+                pass
+            time.sleep(0.02)
+
+    def measure(self, run_for, seconds):
+        """run_for(seconds) keeps the device busy; returns the readings of the second half of that time."""
+        if self._h is None:
+            run_for(0.05)
+            return None
+        self._thread = threading.Thread(target=self._poll, daemon=True)
+        t0 = time.perf_counter()
+        self._thread.start()
+        run_for(seconds)
+        self._stop = True
+        self._thread.join()
+        late = [(c, p) for t, c, p in self.samples if t - t0 > 0.5 * seconds]
+        if not late:
+            return None
+        ck, pw = [c for c, _ in late], [p for _, p in late]
+        return dict(sclk_mhz=round(sum(ck) / len(ck), 1), sclk_mhz_min=min(ck), sclk_mhz_max=max(ck),
+                    socket_power_w=round(sum(pw) / len(pw), 1), power_limit_w=self.limit_w, samples=len(late),
+                    how="amdsmi clock and socket power, polled every 20 ms during %.1f s of back-to-back steps "
+                        "(second half of the readings)" % seconds)
 
 
 def parse():
@@ -46,6 +105,12 @@ def parse():
     p.add_argument("--graph", action="store_true",
                    help="replay a HIP graph of the step instead of launching its kernels one by one from the host "
                         "(measured: no difference, the device queue never runs dry at these kernel durations)")
+    p.add_argument("--profile-mode", action="store_true",
+                   help="only the steps and the per-kernel event pass: no side kernels, no comparison, no CPU leg, "
+                        "no batch timing (whose head-start GEMM launches would mix into counter averages); "
+                        "for runs under rocprofv3")
+    p.add_argument("--state-seconds", type=float, default=1.5,
+                   help="how long the step is repeated to read the device's clock and power under this load")
     p.add_argument("--copy-calibration", action="store_true",
                    help="only run a plain 1 GiB device copy a few times (reference for the "
                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -73,17 +138,26 @@ def run_sweep(args, vq, wl, ceilings):
     specs = wl.config5()
     t0 = time.time()
     layers = []
+    want_cpu = not args.no_cpu_baseline
+    if want_cpu:
+        import oracle
+        oracle.build()
     for s in specs:
         w, bias, sm, cm = wl.draw_weights(s)
         wq, ws = vq.vq_quantize_weight(torch.from_numpy(w).cuda(), None if sm is None else torch.from_numpy(sm).cuda(),
                                        s.w_bits)
-        layers.append(dict(spec=s, wq=wq, ws=ws, bias=torch.from_numpy(bias).cuda(),
-                           cm=None if cm is None else torch.from_numpy(cm).cuda()))
+        L = dict(spec=s, wq=wq, ws=ws, bias=torch.from_numpy(bias).cuda(),
+                 cm=None if cm is None else torch.from_numpy(cm).cuda())
+        if want_cpu:   # the oracle's own weights for its leg below (never the HIP path's)
+            owq, ows = oracle.quantize_weight(w, sm, s.w_bits)
+            L["cpu"] = (owq if s.w_bits == 8 else oracle.pack_int4(owq), ows, bias, cm)
+        layers.append(L)
     # one base activation per input shape, as in the sampled parity test of this configuration
-    base, y, work = {}, {}, {}
+    base, y, work, base_host = {}, {}, {}, {}
     for s in specs:
         if (s.M, s.K) not in base:
-            base[(s.M, s.K)] = torch.from_numpy(wl.draw_x(s)).cuda()
+            base_host[(s.M, s.K)] = wl.draw_x(s)
+            base[(s.M, s.K)] = torch.from_numpy(base_host[(s.M, s.K)]).cuda()
         if (s.M, s.N) not in y:
             y[(s.M, s.N)] = torch.empty((s.M, s.N), dtype=torch.float16, device="cuda")
         key = (s.M, s.N, s.K)
@@ -111,6 +185,15 @@ def run_sweep(args, vq, wl, ceilings):
     ms = (time.perf_counter() - t0) / args.steps * 1e3
     ops = sum(L["spec"].ops for L in layers)
     tops = ops / (ms * 1e-3) / 1e12
+
+    def keep_busy(seconds):
+        t_end = time.perf_counter() + seconds
+        i = 0
+        while time.perf_counter() < t_end:
+            step(1 + i % n_t)
+            i += 1
+            torch.cuda.synchronize()
+    device_state = DeviceState().measure(keep_busy, args.state_seconds)
     # GEMM launches alone, one step, HIP events between the two kernels of every layer
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in layers]
@@ -132,6 +215,29 @@ def run_sweep(args, vq, wl, ceilings):
     q_time = sum(e[0].elapsed_time(e[1]) for _, e in big) * 1e-3
     g_ach, q_ach = g_ops / g_time / 1e12, q_bytes / q_time / 1e9
     n4 = sum(1 for L in layers if L["spec"].w_bits == 4)
+    # ---- the CPU oracle beside it: every layer at denoising steps 1, 10 and 20 on 256 sampled tokens (tokens
+    # are independent, so the sampled rows are exact); a whole step is extrapolated linearly in the token count
+    cpu = None
+    if want_cpu:
+        rows_n = 256
+        t0 = time.perf_counter()
+        c_ops = 0
+        for t in (1, 10, 20):
+            sc = np.float32(wl.config5_step_scale(t))
+            for L in layers:
+                s = L["spec"]
+                g = np.random.default_rng([wl.SEED, 5, t, s.block, s.layer])
+                rows = np.sort(g.choice(s.M, min(rows_n, s.M), replace=False))
+                x = (base_host[(s.M, s.K)][rows].astype(np.float32) * sc).astype(np.float16)
+                wdev, ows, bias, cm = L["cpu"]
+                oracle.linear(x, cm, wdev, s.w_bits, ows, bias)
+                c_ops += 2 * len(rows) * s.N * s.K
+        dt = time.perf_counter() - t0
+        cpu = dict(value=round(c_ops / dt / 1e12, 6), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+                   sample="all 168 layers at denoising steps 1, 10 and 20 on %d seeded sample tokens each (all tokens of "
+                          "the 240-token layers), whole layer (quantize + integer GEMM + dequantize), %.1f s; extrapolated "
+                          "linearly in the token count a whole step would take %.0f s" % (rows_n, dt, ops / (c_ops / dt)))
+        log(f"cpu oracle: {c_ops / dt / 1e9:.1f} GOP/s on {cpu['cores']} threads ({dt:.1f} s)")
     out = {
         "metric": "quantized-linear int8 TOPS (quant+GEMM+dequant)", "value": round(tops, 2), "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
@@ -146,9 +252,18 @@ def run_sweep(args, vq, wl, ceilings):
                          launches="the %d GEMM launches with M >= 1024 of one step, HIP-event durations" % len(big)),
         "roofline_quantizer": dict(kernel="quantize_tokens_wave", bound="hbm", achieved=round(q_ach, 1), peak=HBM_PEAK_GBS,
                                    unit="GB/s", frac=round(q_ach / HBM_PEAK_GBS, 4), traffic=None),
-        "cpu_baseline": None,
+        "device_state": device_state,
+        "csrc_sha256": csrc_hash(),
+        "cpu_baseline": cpu,
         "measured_ceilings": ceilings,
     }
+    if ceilings:
+        c32 = ceilings["mfma_only_tops_activation_like_x_weight_like"]
+        c16 = ceilings.get("mfma_only_tops_16x16x64_activation_like_x_weight_like", 0)
+        out["roofline"]["measured_mfma_only_ceiling"] = max(c32, c16)
+        out["roofline"]["frac_of_measured_ceiling"] = round(g_ach / max(c32, c16), 4)
+        out["roofline_quantizer"]["measured_copy_ceiling"] = ceilings["copy_1gib_read_plus_write_gbs"]
+        out["roofline_quantizer"]["frac_of_measured_ceiling"] = round(q_ach / ceilings["copy_1gib_read_plus_write_gbs"], 4)
     log(f"sweep: {ms:.2f} ms per denoising step, {tops:.0f} TOPS; GEMM launches {g_ach:.0f} TOP/s, quantizer {q_ach:.0f} GB/s")
     print(json.dumps(out), flush=True)
 
@@ -164,6 +279,8 @@ def quant_bytes(s, has_mul):
 
 def main():
     args = parse()
+    if args.profile_mode:
+        args.no_fused = args.no_cpu_baseline = args.no_ceilings = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the layer shards by tokens with no exchange; "
                  "nothing here uses a second device). Run with --gpus 1.")
@@ -252,6 +369,17 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     total_ops = sum(L["spec"].ops for L in layers)
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- what the device does under this load: core clock and socket power while the step repeats -----
+    def keep_busy(seconds):
+        t_end = time.perf_counter() + seconds
+        while time.perf_counter() < t_end:
+            for _ in range(20):
+                step()
+            torch.cuda.synchronize()
+    device_state = None if args.profile_mode else DeviceState().measure(keep_busy, args.state_seconds)
+    if device_state:
+        log("device under the step: %(sclk_mhz).0f MHz core clock, %(socket_power_w).0f W of %(power_limit_w).0f W" % device_state)
 
     # ---- per-kernel durations: the same launches, HIP events on the launch stream ---------------
     # (the two kernels vq_linear enqueues, called one by one so that events can sit between them)
@@ -343,7 +471,7 @@ def main():
 
     def quantizer_of(L):
         return lambda: vq.vq_quantize_per_token(L["x"], L["cm"], xq=L["xq"], x_scale=L["xs"])
-    q_time = timed_batch([quantizer_of(L) for L, _ in big])
+    q_time = None if args.profile_mode else timed_batch([quantizer_of(L) for L, _ in big])
     # Three readings of the same launches: each between its own pair of events inside the step (includes the
     # 2-3 us between a GEMM and the next launch: conservative, and the conditions of the timed region), all of them
     # back to back between one pair of events (no GEMMs in between: a long run of memory-bound launches), and the
@@ -353,11 +481,11 @@ def main():
                       peak=HBM_PEAK_GBS, unit="GB/s", frac=round(q_achieved / HBM_PEAK_GBS, 4), traffic=None,
                       launches="the %d quantizer launches with M >= 1024 inside the step, each between its own pair of HIP "
                                "events; bytes = 3MK + 4M (+4K) each" % len(big),
-                      back_to_back_GBps=round(q_bytes / q_time / 1e9, 1),
+                      back_to_back_GBps=None if q_time is None else round(q_bytes / q_time / 1e9, 1),
                       back_to_back_note="the same launches (distinct inputs, %.0f MB) back to back between one pair of "
                                         "events, %d passes" % (sum(2 * L["spec"].M * L["spec"].K for L, _ in big) / 1e6, nrep))
-    log(f"quantizer, {len(big)} launches: {q_achieved:.0f} GB/s inside the step (event pair per launch), "
-        f"{q_bytes / q_time / 1e9:.0f} GB/s back to back")
+    log(f"quantizer, {len(big)} launches: {q_achieved:.0f} GB/s inside the step (event pair per launch)"
+        + ("" if q_time is None else f", {q_bytes / q_time / 1e9:.0f} GB/s back to back"))
 
     # ---- the quantizer fused behind its producer, on the same activations ----------------------
     # (not part of the step: LayerNorm + modulation feeds qkv and fc1, GELU feeds fc2, the residual
@@ -492,20 +620,34 @@ def main():
         log(f"cpu oracle: {ops / dt / 1e9:.1f} GOP/s on {cpu['cores']} threads ({dt:.1f} s, {rows_big} tokens/layer)")
 
     # HBM bytes per launch as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in separate runs of this
-    # same command (the counters cannot be read from inside a run); the summary names the commands.
-    traffic_file = os.path.join(ROOT, "profiles", "gemm_traffic_video_w8a8.json")
-    if args.workload == "video" and os.path.exists(traffic_file):
-        t = json.load(open(traffic_file))
-        roofline["traffic"] = t["fetch_bytes"] + t["write_bytes"]  # HBM bytes per launch, read + written
-        roofline["traffic_detail"] = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
-                                      "algorithmic_bytes": int(sum(gemm_bytes(L["spec"]) for L, _ in big) / len(big)),
-                                      "per": "launch, average over the %d large layers" % len(big),
-                                      "source": t["source"]}
-    qtrace_file = os.path.join(ROOT, "profiles", "quantizer_trace_video_w8a8.json")
-    if args.workload == "video" and os.path.exists(qtrace_file):
+    # same command with --profile-mode (the counters cannot be read from inside a run).  The summary names the
+    # commands and carries the hash of the kernel sources it was taken with: a summary of other sources is not used.
+    cfile = os.path.join(ROOT, "profiles", "gemm_counters_%s.json" % args.workload.replace("-", "_"))
+    if os.path.exists(cfile):
+        t = json.load(open(cfile))
+        if t.get("csrc_sha256") == csrc_hash():
+            rows = [t["layers"][L["spec"].name] for L, _ in big if L["spec"].name in t["layers"]]
+            if len(rows) == len(big):
+                roofline["traffic"] = int(sum(r["fetch_bytes"] + r["write_bytes"] for r in rows) / len(rows))
+                roofline["traffic_detail"] = {
+                    "per": "launch, average over the %d large layers (HBM/fabric bytes read + written)" % len(big),
+                    "algorithmic_bytes": int(sum(gemm_bytes(L["spec"]) for L, _ in big) / len(big)),
+                    "per_layer": {L["spec"].name: dict(fetch_bytes=r["fetch_bytes"], write_bytes=r["write_bytes"],
+                                                       algorithmic_read=gemm_bytes(L["spec"]) - 2 * L["spec"].M * L["spec"].N,
+                                                       algorithmic_write=2 * L["spec"].M * L["spec"].N)
+                                  for (L, _), r in zip(big, rows)},
+                    "counters": {k: t[k] for k in ("mfma_busy_frac", "clock_ghz_under_counters") if k in t},
+                    "source": t["source"], "csrc_sha256": t["csrc_sha256"]}
+        else:
+            log("profiles/%s was taken with other kernel sources (%s, now %s): traffic stays null"
+                % (os.path.basename(cfile), t.get("csrc_sha256"), csrc_hash()))
+    qtrace_file = os.path.join(ROOT, "profiles", "quantizer_trace_%s.json" % args.workload.replace("-", "_"))
+    if os.path.exists(qtrace_file):
         # the kernel's own durations inside the steps, from the committed rocprofv3 kernel trace of this command
         # (events cannot leave out the gaps between launches, which weigh on a 20 us kernel)
-        roofline_q["kernel_trace"] = json.load(open(qtrace_file))
+        qt = json.load(open(qtrace_file))
+        if qt.get("csrc_sha256") == csrc_hash():
+            roofline_q["kernel_trace"] = qt
     if ceilings:
         # what a loop of nothing but MFMAs sustains on such operands, with the shape this kernel uses and with
         # the other int8 shape (which moves fewer accumulator registers and sustains more); the fraction is
@@ -537,6 +679,8 @@ def main():
         "frac_of_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
         "roofline": roofline,
         "roofline_quantizer": roofline_q,
+        "device_state": device_state,
+        "csrc_sha256": csrc_hash(),
         "cpu_baseline": cpu,
         "fused_quantizers": fused,
         "comparison": comparison,
