@@ -13,7 +13,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libvidiq.so")
 CEILINGS_PATH = os.path.join(PKG_DIR, "vq_ceilings")  # stand-alone program, see csrc/vq_ceilings.hip
-SOURCES = ["vq_api.hip", "vq_quantize.hip", "vq_fused.hip", "vq_gemm.hip", "vq_gemm_192.hip", "vq_gemm_small.hip"]
+SOURCES = ["vq_api.hip", "vq_quantize.hip", "vq_fused.hip", "vq_fused_gelu.hip", "vq_gemm.hip", "vq_gemm_192.hip", "vq_gemm_small.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
