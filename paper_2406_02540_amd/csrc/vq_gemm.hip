@@ -40,13 +40,9 @@ hipError_t launch_gemm(const int8_t* xq, const float* x_scale, const void* w, in
     a.N = N;
     a.K = K;
     a.tiles_t = a.tiles_c = a.tiles = a.tiles_per_xcd = a.slots = 0;  // (set for the chosen tile)
-    // The narrower tile moves a sixth more operand bytes per multiply-add: it has to save
-    // more than that in rounds (VQ_GEMM_TILE_MARGIN) to be chosen.
-#ifdef VQ_GEMM_FORCE_TILE
-    const bool narrow = VQ_GEMM_FORCE_TILE == 192;
-#else
+    // The narrower tile moves a sixth more operand bytes per multiply-add and is chosen only
+    // where it saves rounds of tiles.
     const bool narrow = rounds_cost(M, N, 192, num_cus) * 1.05 < rounds_cost(M, N, 256, num_cus);
-#endif
     if (narrow) return launch_gemm_192(a, w_bits, num_cus, stream);
     return launch_gemm_shape<Tile256>(a, w_bits, num_cus, stream);
 }
