@@ -223,6 +223,34 @@ int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bit
 size_t vq_linear_workspace_bytes(int M, int N, int K, int w_bits);
 
 /*
+ * The layer behind one of the producers (Sec. 5.1 "Hardware Implementation Settings": the
+ * quantizer is merged into the LayerNorm, GELU or residual operation that precedes the linear
+ * layer; Sec. 4.2 for the rotation): the fused quantizer of the same name into the workspace,
+ * then the GEMM that w_bits selects.  The producer's arguments are those of
+ * vq_layernorm_quantize / vq_gelu_quantize / vq_residual_quantize / vq_hadamard_quantize, the
+ * rest those of vq_linear (same workspace size), and the results are bit for bit those of the
+ * two separate calls.  K as the fused quantizers need it (K % 8 == 0, K <= VQ_MAX_FUSED_K,
+ * K % 128 == 0 for the rotation) and as the GEMM needs it (K % 16, K % 32 for 4-bit weights).
+ * vq_residual_linear also writes the new residual stream r_f16 [M,K].  For
+ * vq_hadamard_linear the weights must have been rotated (vq_rotate_weight) before they
+ * were quantized.
+ */
+int vq_layernorm_linear(const void* x_f16, const float* mod_scale, const float* mod_shift,
+                        int tokens_per_sample, float eps, const float* chan_mul, const void* w, int w_bits,
+                        const float* w_scale, const void* bias_f16, void* y_f16,
+                        void* workspace, size_t workspace_bytes, int M, int N, int K, void* hip_stream);
+int vq_gelu_linear(const void* h_f16, int approximate, const float* chan_mul, const void* w, int w_bits,
+                   const float* w_scale, const void* bias_f16, void* y_f16,
+                   void* workspace, size_t workspace_bytes, int M, int N, int K, void* hip_stream);
+int vq_residual_linear(const void* x_f16, const void* y_in_f16, const float* gate, int tokens_per_sample,
+                       void* r_f16, const float* chan_mul, const void* w, int w_bits, const float* w_scale,
+                       const void* bias_f16, void* y_f16,
+                       void* workspace, size_t workspace_bytes, int M, int N, int K, void* hip_stream);
+int vq_hadamard_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
+                       const float* w_scale, const void* bias_f16, void* y_f16,
+                       void* workspace, size_t workspace_bytes, int M, int N, int K, void* hip_stream);
+
+/*
  * vq_linear without a workspace argument, for callers that cannot allocate device memory
  * around the call (code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc).  The int8 activations and token scales live in a scratch array built into the

@@ -37,6 +37,10 @@ SIGNATURES = {
     "vq_gemm_w4a8": (_I, [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _P]),
     "vq_linear": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
     "vq_linear_workspace_bytes": (_SZ, [_I, _I, _I, _I]),
+    "vq_layernorm_linear": (_I, [_P, _P, _P, _I, ctypes.c_float, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
+    "vq_gelu_linear": (_I, [_P, _I, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
+    "vq_residual_linear": (_I, [_P, _P, _P, _I, _P, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
+    "vq_hadamard_linear": (_I, [_P, _P, _P, _I, _P, _P, _P, _P, _SZ, _I, _I, _I, _P]),
     "vq_linear_static": (_I, [_P, _P, _P, _I, _P, _P, _P, _I, _I, _I, _P]),
     "vq_quantize_weight": (_I, [_P, _P, _I, _P, _P, _I, _I, _P]),
     "vq_status_string": (ctypes.c_char_p, [_I]),
@@ -360,16 +364,80 @@ def vq_linear_static(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, stream=
     return y
 
 
+def _workspace(workspace, x, M, N, K, w_bits):
+    if workspace is None:
+        need = vq_linear_workspace_bytes(M, N, K, w_bits)
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=x.device)
+    return _dev(workspace, torch.uint8, "workspace")
+
+
 def vq_linear(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, workspace=None, stream=None):
     """The whole layer on fp16 activations; workspace is a uint8 device tensor (allocated if None)."""
     x, chan_mul, w, w_scale, bias, y, M, N, K = _linear_args(x, chan_mul, w, w_bits, w_scale, bias, y, "vq_linear")
-    need = vq_linear_workspace_bytes(M, N, K, w_bits)
-    if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
+    workspace = _workspace(workspace, x, M, N, K, w_bits)
     _check(lib().vq_linear(_ptr(x), _ptr(chan_mul), _ptr(w), int(w_bits), _ptr(w_scale), _ptr(bias),
                            _ptr(y), _ptr(workspace), workspace.numel(), M, N, K, _stream(stream)),
            "vq_linear")
+    return y
+
+
+def vq_layernorm_linear(x, w, w_bits, w_scale, mod_scale=None, mod_shift=None, tokens_per_sample=None, eps=1e-6,
+                        chan_mul=None, bias=None, y=None, workspace=None, stream=None):
+    """LayerNorm + modulation, quantizer and GEMM in one call: x fp16 [M,K] -> y fp16 [M,N]."""
+    x, chan_mul, w, w_scale, bias, y, M, N, K = _linear_args(x, chan_mul, w, w_bits, w_scale, bias, y,
+                                                             "vq_layernorm_linear")
+    T = int(tokens_per_sample) if tokens_per_sample else max(M, 1)
+    mod_scale = _per_sample(mod_scale, M, K, T, "mod_scale")
+    mod_shift = _per_sample(mod_shift, M, K, T, "mod_shift")
+    workspace = _workspace(workspace, x, M, N, K, w_bits)
+    _check(lib().vq_layernorm_linear(_ptr(x), _ptr(mod_scale), _ptr(mod_shift), T, float(eps), _ptr(chan_mul),
+                                     _ptr(w), int(w_bits), _ptr(w_scale), _ptr(bias), _ptr(y), _ptr(workspace),
+                                     workspace.numel(), M, N, K, _stream(stream)), "vq_layernorm_linear")
+    return y
+
+
+def vq_gelu_linear(h, w, w_bits, w_scale, approximate=False, chan_mul=None, bias=None, y=None, workspace=None,
+                   stream=None):
+    """GELU, quantizer and GEMM in one call: h fp16 [M,K] -> y fp16 [M,N]."""
+    h, chan_mul, w, w_scale, bias, y, M, N, K = _linear_args(h, chan_mul, w, w_bits, w_scale, bias, y,
+                                                             "vq_gelu_linear")
+    workspace = _workspace(workspace, h, M, N, K, w_bits)
+    _check(lib().vq_gelu_linear(_ptr(h), int(bool(approximate)), _ptr(chan_mul), _ptr(w), int(w_bits),
+                                _ptr(w_scale), _ptr(bias), _ptr(y), _ptr(workspace), workspace.numel(), M, N, K,
+                                _stream(stream)), "vq_gelu_linear")
+    return y
+
+
+def vq_residual_linear(x, y_in, w, w_bits, w_scale, gate=None, tokens_per_sample=None, r=None, chan_mul=None,
+                       bias=None, y=None, workspace=None, stream=None):
+    """r = x + gate * y_in, quantizer and GEMM in one call: fp16 [M,K] twice -> (r fp16 [M,K], y fp16 [M,N])."""
+    x, chan_mul, w, w_scale, bias, y, M, N, K = _linear_args(x, chan_mul, w, w_bits, w_scale, bias, y,
+                                                             "vq_residual_linear")
+    y_in = _dev(y_in, torch.float16, "y_in")
+    if y_in is None or tuple(y_in.shape) != (M, K):
+        raise ValueError("y_in must have the shape of x")
+    T = int(tokens_per_sample) if tokens_per_sample else max(M, 1)
+    gate = _per_sample(gate, M, K, T, "gate")
+    if r is None:
+        r = torch.empty((M, K), dtype=torch.float16, device=x.device)
+    _dev(r, torch.float16, "r")
+    if tuple(r.shape) != (M, K):
+        raise ValueError("r must have the shape of x")
+    workspace = _workspace(workspace, x, M, N, K, w_bits)
+    _check(lib().vq_residual_linear(_ptr(x), _ptr(y_in), _ptr(gate), T, _ptr(r), _ptr(chan_mul), _ptr(w),
+                                    int(w_bits), _ptr(w_scale), _ptr(bias), _ptr(y), _ptr(workspace),
+                                    workspace.numel(), M, N, K, _stream(stream)), "vq_residual_linear")
+    return r, y
+
+
+def vq_hadamard_linear(x, chan_mul, w, w_bits, w_scale, bias=None, y=None, workspace=None, stream=None):
+    """Scaling, block Hadamard rotation, quantizer and GEMM in one call (w quantized from rotated weights)."""
+    x, chan_mul, w, w_scale, bias, y, M, N, K = _linear_args(x, chan_mul, w, w_bits, w_scale, bias, y,
+                                                             "vq_hadamard_linear")
+    workspace = _workspace(workspace, x, M, N, K, w_bits)
+    _check(lib().vq_hadamard_linear(_ptr(x), _ptr(chan_mul), _ptr(w), int(w_bits), _ptr(w_scale), _ptr(bias),
+                                    _ptr(y), _ptr(workspace), workspace.numel(), M, N, K, _stream(stream)),
+           "vq_hadamard_linear")
     return y
 
 

@@ -121,6 +121,40 @@ int validate_fused(const void* x, const void* chan_mul, const void* xq, const vo
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Shared by the layer entry points that take a workspace: validates the layer, splits the
+// workspace into xq and x_scale, lets `quantize` enqueue the (plain or fused) quantizer into
+// them and enqueues the GEMM behind it.  `fused`: the quantizer is one of the fused ones, which
+// hold a token in registers (K % 8 == 0, K <= VQ_MAX_FUSED_K).
+template <class Quantize>
+int linear_through_workspace(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
+                             const float* w_scale, const void* bias_f16, void* y_f16, void* workspace,
+                             size_t workspace_bytes, int M, int N, int K, void* hip_stream, bool fused,
+                             Quantize quantize) {
+    if (w_bits != 8 && w_bits != 4) return VQ_ERR_BITS;
+    if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K) return VQ_ERR_SHAPE;
+    if (K % (w_bits == 8 ? 16 : 32) != 0) return VQ_ERR_SHAPE;
+    if (fused && K > VQ_MAX_FUSED_K) return VQ_ERR_SHAPE;
+    if (M == 0 || N == 0) return VQ_OK;
+    if (!workspace) return VQ_ERR_NULL;
+    if (misaligned(workspace)) return VQ_ERR_ALIGN;
+    if (workspace_bytes < vq_linear_workspace_bytes(M, N, K, w_bits)) return VQ_ERR_WORKSPACE;
+    int8_t* xq = (int8_t*)workspace;
+    float* x_scale = (float*)((char*)workspace + round_up((size_t)M * (size_t)K, kAlign));
+    // validate both halves before anything is enqueued
+    int v = validate_quantize(x_f16, chan_mul, xq, x_scale, M, K);
+    if (v != VQ_OK) return v;
+    v = validate_gemm(xq, x_scale, w, w_scale, bias_f16, y_f16, nullptr, w_bits, M, N, K);
+    if (v != VQ_OK) return v;
+    int num_cus = 0;
+    const int arch = check_arch(&num_cus);
+    if (arch != VQ_OK) return arch;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    v = launch_status(quantize(xq, x_scale, stream));
+    if (v != VQ_OK) return v;
+    return launch_status(vq::launch_gemm(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, nullptr,
+                                         M, N, K, num_cus, stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -267,28 +301,60 @@ size_t vq_linear_workspace_bytes(int M, int N, int K, int w_bits) {
 int vq_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
               const float* w_scale, const void* bias_f16, void* y_f16, void* workspace,
               size_t workspace_bytes, int M, int N, int K, void* hip_stream) {
-    if (w_bits != 8 && w_bits != 4) return VQ_ERR_BITS;
-    if (M < 0 || N < 0 || K <= 0 || K > VQ_MAX_K) return VQ_ERR_SHAPE;
-    if (K % (w_bits == 8 ? 16 : 32) != 0) return VQ_ERR_SHAPE;
-    if (M == 0 || N == 0) return VQ_OK;
-    if (!workspace) return VQ_ERR_NULL;
-    if (misaligned(workspace)) return VQ_ERR_ALIGN;
-    if (workspace_bytes < vq_linear_workspace_bytes(M, N, K, w_bits)) return VQ_ERR_WORKSPACE;
-    int8_t* xq = (int8_t*)workspace;
-    float* x_scale = (float*)((char*)workspace + round_up((size_t)M * (size_t)K, kAlign));
-    // validate both halves before anything is enqueued
-    int v = validate_quantize(x_f16, chan_mul, xq, x_scale, M, K);
-    if (v != VQ_OK) return v;
-    v = validate_gemm(xq, x_scale, w, w_scale, bias_f16, y_f16, nullptr, w_bits, M, N, K);
-    if (v != VQ_OK) return v;
-    int num_cus = 0;
-    const int arch = check_arch(&num_cus);
-    if (arch != VQ_OK) return arch;
-    hipStream_t stream = (hipStream_t)hip_stream;
-    v = launch_status(vq::launch_quantize_per_token(x_f16, chan_mul, xq, x_scale, M, K, stream));
-    if (v != VQ_OK) return v;
-    return launch_status(vq::launch_gemm(xq, x_scale, w, w_bits, w_scale, bias_f16, y_f16, nullptr,
-                                         M, N, K, num_cus, stream));
+    return linear_through_workspace(x_f16, chan_mul, w, w_bits, w_scale, bias_f16, y_f16, workspace, workspace_bytes,
+                                    M, N, K, hip_stream, false, [&](int8_t* xq, float* x_scale, hipStream_t stream) {
+                                        return vq::launch_quantize_per_token(x_f16, chan_mul, xq, x_scale, M, K, stream);
+                                    });
+}
+
+int vq_layernorm_linear(const void* x_f16, const float* mod_scale, const float* mod_shift,
+                        int tokens_per_sample, float eps, const float* chan_mul, const void* w, int w_bits,
+                        const float* w_scale, const void* bias_f16, void* y_f16, void* workspace,
+                        size_t workspace_bytes, int M, int N, int K, void* hip_stream) {
+    if (tokens_per_sample <= 0 || !(eps >= 0.0f)) return VQ_ERR_SHAPE;
+    if ((mod_scale && misaligned(mod_scale)) || (mod_shift && misaligned(mod_shift))) return VQ_ERR_ALIGN;
+    return linear_through_workspace(x_f16, chan_mul, w, w_bits, w_scale, bias_f16, y_f16, workspace, workspace_bytes,
+                                    M, N, K, hip_stream, true, [&](int8_t* xq, float* x_scale, hipStream_t stream) {
+                                        return vq::launch_layernorm_quantize(x_f16, mod_scale, mod_shift, tokens_per_sample,
+                                                                             eps, chan_mul, xq, x_scale, M, K, stream);
+                                    });
+}
+
+int vq_gelu_linear(const void* h_f16, int approximate, const float* chan_mul, const void* w, int w_bits,
+                   const float* w_scale, const void* bias_f16, void* y_f16, void* workspace,
+                   size_t workspace_bytes, int M, int N, int K, void* hip_stream) {
+    if (approximate != 0 && approximate != 1) return VQ_ERR_SHAPE;
+    return linear_through_workspace(h_f16, chan_mul, w, w_bits, w_scale, bias_f16, y_f16, workspace, workspace_bytes,
+                                    M, N, K, hip_stream, true, [&](int8_t* xq, float* x_scale, hipStream_t stream) {
+                                        return vq::launch_gelu_quantize(h_f16, approximate, chan_mul, xq, x_scale, M, K,
+                                                                        stream);
+                                    });
+}
+
+int vq_residual_linear(const void* x_f16, const void* y_in_f16, const float* gate, int tokens_per_sample,
+                       void* r_f16, const float* chan_mul, const void* w, int w_bits, const float* w_scale,
+                       const void* bias_f16, void* y_f16, void* workspace, size_t workspace_bytes, int M, int N,
+                       int K, void* hip_stream) {
+    if (tokens_per_sample <= 0) return VQ_ERR_SHAPE;
+    if (M > 0 && N > 0) {
+        if (!y_in_f16 || !r_f16) return VQ_ERR_NULL;
+        if (misaligned(y_in_f16) || misaligned(r_f16) || (gate && misaligned(gate))) return VQ_ERR_ALIGN;
+    }
+    return linear_through_workspace(x_f16, chan_mul, w, w_bits, w_scale, bias_f16, y_f16, workspace, workspace_bytes,
+                                    M, N, K, hip_stream, true, [&](int8_t* xq, float* x_scale, hipStream_t stream) {
+                                        return vq::launch_residual_quantize(x_f16, y_in_f16, gate, tokens_per_sample,
+                                                                            r_f16, chan_mul, xq, x_scale, M, K, stream);
+                                    });
+}
+
+int vq_hadamard_linear(const void* x_f16, const float* chan_mul, const void* w, int w_bits,
+                       const float* w_scale, const void* bias_f16, void* y_f16, void* workspace,
+                       size_t workspace_bytes, int M, int N, int K, void* hip_stream) {
+    if (K > 0 && K % VQ_HADAMARD_BLOCK != 0) return VQ_ERR_SHAPE;
+    return linear_through_workspace(x_f16, chan_mul, w, w_bits, w_scale, bias_f16, y_f16, workspace, workspace_bytes,
+                                    M, N, K, hip_stream, true, [&](int8_t* xq, float* x_scale, hipStream_t stream) {
+                                        return vq::launch_hadamard_quantize(x_f16, chan_mul, xq, x_scale, M, K, stream);
+                                    });
 }
 
 int vq_linear_static(const void* x_f16, const float* chan_mul, const void* w, int w_bits,

@@ -262,3 +262,87 @@ def test_hadamard_calls_rejected(vq):
     assert e.value.status == 2
     with pytest.raises(VqError):
         vq.vq_rotate_weight(torch.zeros((4, 192), device="cuda"))
+
+
+# ---- the layer behind a producer in one call: bit for bit the two separate calls -------------
+
+LAYER_SHAPES = [(8, 300, 264, 1152), (4, 300, 264, 1152), (8, 517, 392, 640), (4, 130, 1160, 4608),
+                (8, 2900, 2824, 1152), (8, 1, 8, 128)]
+
+
+def _layer(seed, bits, M, N, K, oracle):
+    g = np.random.default_rng(seed)
+    x = (g.standard_normal((M, K)) * g.uniform(0.1, 8, (M, 1))).astype(np.float16)
+    w = (g.standard_normal((N, K)) * 0.03).astype(np.float32)
+    s = np.exp(g.uniform(np.log(0.5), np.log(2), K)).astype(np.float32)
+    b = (g.standard_normal(N) * 0.05).astype(np.float16)
+    return g, x, w, s, (np.float32(1) / s).astype(np.float32), b
+
+
+@pytest.mark.parametrize("bits,M,N,K", LAYER_SHAPES)
+def test_producer_linear_equals_the_two_calls(vq, oracle, bits, M, N, K):
+    say(f"producer linear bits={bits} M={M} N={N} K={K}")
+    g, x, w, s, cm, b = _layer(7000 + M + N + K + bits, bits, M, N, K, oracle)
+    gemm = vq.vq_gemm_w8a8 if bits == 8 else vq.vq_gemm_w4a8
+    wq, ws = vq.vq_quantize_weight(dev(w), dev(s), bits)
+    T = max(1, M // 2)
+    B = (M + T - 1) // T
+    sc = (g.standard_normal((B, K)) * 0.3).astype(np.float32)
+    sh = (g.standard_normal((B, K)) * 0.5).astype(np.float32)
+    gate = g.standard_normal((B, K)).astype(np.float32)
+    y_in = (g.standard_normal((M, K)) * 0.7).astype(np.float16)
+    dx, dcm, db = dev(x), dev(cm), dev(b)
+
+    q, xs = vq.vq_layernorm_quantize(dx, dev(sc), dev(sh), T, 1e-6, dcm)
+    want = gemm(q, xs, wq, ws, db)
+    got = vq.vq_layernorm_linear(dx, wq, bits, ws, dev(sc), dev(sh), T, 1e-6, dcm, db)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+
+    for approximate in (False, True):
+        q, xs = vq.vq_gelu_quantize(dx, approximate, dcm)
+        want = gemm(q, xs, wq, ws, db)
+        got = vq.vq_gelu_linear(dx, wq, bits, ws, approximate, dcm, db)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want)
+
+    r_want, q, xs = vq.vq_residual_quantize(dx, dev(y_in), dev(gate), T, None, dcm)
+    want = gemm(q, xs, wq, ws, db)
+    r_got, got = vq.vq_residual_linear(dx, dev(y_in), wq, bits, ws, dev(gate), T, None, dcm, db)
+    torch.cuda.synchronize()
+    assert torch.equal(r_got, r_want) and torch.equal(got, want)
+    # this producer is fully determined: the oracle's layer on the oracle's residual stream
+    r_ref, _, _ = oracle.residual_quantize(x, y_in, gate, T, cm)
+    assert np.array_equal(host(r_got).view(np.uint16), r_ref.view(np.uint16))
+    rows_ = np.unique(np.concatenate([[0, M - 1], g.integers(0, M, 24)]))
+    wq_ref, ws_ref = oracle.quantize_weight(w, s, bits)
+    assert np.array_equal(host(ws).view(np.uint32), ws_ref.view(np.uint32))
+    ref = oracle.linear(r_ref[rows_], cm, wq_ref if bits == 8 else oracle.pack_int4(wq_ref), bits, ws_ref, b)
+    from parity_util import assert_fp16_close
+    assert_fp16_close(host(got)[rows_], ref["y"], ref["acc"], ref["x_scale"], ws_ref, b)
+
+    if K % 128 == 0:
+        w_rot = vq.vq_rotate_weight(dev(w), dev(s))
+        wq_r, ws_r = vq.vq_quantize_weight(w_rot, None, bits)
+        q, xs = vq.vq_hadamard_quantize(dx, dcm)
+        want = gemm(q, xs, wq_r, ws_r, db)
+        got = vq.vq_hadamard_linear(dx, dcm, wq_r, bits, ws_r, db)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want)
+
+
+def test_producer_linear_rejected_or_empty(vq):
+    from paper_2406_02540_amd.binding import VqError
+    w = torch.zeros((8, 192), dtype=torch.int8, device="cuda")
+    ws = torch.ones((8,), dtype=torch.float32, device="cuda")
+    x = torch.zeros((4, 192), dtype=torch.float16, device="cuda")
+    with pytest.raises(VqError) as e:
+        vq.vq_hadamard_linear(x, None, w, 8, ws)       # K not whole blocks of 128
+    assert e.value.status == 2
+    with pytest.raises(VqError) as e:
+        vq.vq_gelu_linear(x, w, 8, ws, workspace=torch.zeros((64,), dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 4
+    empty = torch.zeros((0, 192), dtype=torch.float16, device="cuda")
+    assert vq.vq_layernorm_linear(empty, w, 8, ws).shape == (0, 8)
+    r, y = vq.vq_residual_linear(empty, empty, w, 8, ws)
+    assert r.shape == (0, 192) and y.shape == (0, 8)

@@ -180,6 +180,44 @@ def test_linear_argument_errors(lib):
     assert call(M=0) == 0
 
 
+def test_producer_linear_argument_errors(lib):
+    """The layer behind a producer: the producer's checks, then those of vq_linear."""
+    F = ctypes.c_float
+    need = lib.vq_linear_workspace_bytes(4, 8, 256, 8)
+    tail = dict(cm=None, w=P(A), bits=8, ws=P(A), b=None, y=P(A), wk=P(A), wb=need, M=4, N=8, K=256)
+
+    def tail_args(a):
+        return (a["cm"], a["w"], a["bits"], a["ws"], a["b"], a["y"], a["wk"], a["wb"], a["M"], a["N"], a["K"], None)
+
+    def ln(x=P(A), sc=None, sh=None, T=2, eps=1e-6, **kw):
+        return lib.vq_layernorm_linear(x, sc, sh, T, F(eps), *tail_args(dict(tail, **kw)))
+
+    def ge(h=P(A), approx=1, **kw):
+        return lib.vq_gelu_linear(h, approx, *tail_args(dict(tail, **kw)))
+
+    def rs(x=P(A), yin=P(A), gate=None, T=2, r=P(A), **kw):
+        return lib.vq_residual_linear(x, yin, gate, T, r, *tail_args(dict(tail, **kw)))
+
+    def hd(x=P(A), **kw):
+        return lib.vq_hadamard_linear(x, *tail_args(dict(tail, **kw)))
+
+    for f in (ln, ge, rs, hd):
+        assert f(bits=5) == 7
+        assert f(K=24) == 2 and f(bits=4, K=48) == 2
+        assert f(K=8192 + 128) == 2                      # the fused quantizers hold the token in registers
+        assert f(wk=None) == 1 and f(wk=P(A + 4)) == 3 and f(wb=need - 1) == 4
+        assert f(w=None) == 1 and f(ws=None) == 1 and f(y=None) == 1
+        assert f(b=P(A + 2)) == 3 and f(cm=P(A + 4)) == 3
+        assert f(M=0) == 0 and f(N=0) == 0
+        assert f() == 6                                  # valid arguments reach the device check
+    assert ln(x=None) == 1 and ge(h=None) == 1 and rs(x=None) == 1 and hd(x=None) == 1
+    assert ln(T=0) == 2 and ln(eps=-1.0) == 2 and ln(sc=P(A + 4)) == 3 and ln(sh=P(A + 8)) == 3
+    assert ge(approx=2) == 2
+    assert rs(T=0) == 2 and rs(yin=None) == 1 and rs(r=None) == 1 and rs(gate=P(A + 4)) == 3 and rs(r=P(A + 2)) == 3
+    assert hd(K=192) == 2                                # whole blocks of 128 channels
+    assert ge(K=64, wb=lib.vq_linear_workspace_bytes(4, 8, 64, 8)) == 6
+
+
 def test_quantize_weight_argument_errors(lib):
     f = lib.vq_quantize_weight
     assert f(P(A), None, 3, P(A), P(A), 4, 64, None) == 7
