@@ -156,7 +156,8 @@ int vq_rotate_weight(const float* w_f32, const float* chan_s, float* w_rot_f32, 
  * tiling as vq_gemm_w8a8.  They are measured next to the quantized layer, not part of it.
  *
  * vq_gemm_f16:        y[m,n] = fp16(sum_k x[m,k] * w[n,k] + bias[n]), fp16 operands,
- *                     products exact, sums in fp32 (matrix-core order).  x_f16 [M,K],
+ *                     products exact, sums in fp32 (matrix-core order), the bias added to
+ *                     the fp32 sum exactly and the result rounded once.  x_f16 [M,K],
  *                     w_f16 [N,K], bias_f16 [N] or NULL, y_f16 [M,N]; K % 8 == 0.
  * vq_quantize_static: xq[m,k] = clamp(rne(float(x[m,k]) * chan_mul[k] * (1 / scale)),
  *                     -127, 127) with one `scale` (host value, > 0) for the whole tensor
@@ -176,6 +177,8 @@ int vq_quantize_static(const void* x_f16, const float* chan_mul, float scale, in
  *
  *   acc[m,n] = sum_k xq[m,k] * wq[n,k]                       (exact, int32)
  *   y[m,n]   = fp16(float(acc[m,n]) * x_scale[m] * w_scale[n] + float(bias[n]))
+ * evaluated as: s = x_scale[m] * w_scale[n] rounded to fp32, then float(acc) * s + bias
+ * exactly, rounded once (to nearest even) to fp16; whichever kernel the library picks.
  *
  *   xq       in  int8 [M,K]          x_scale in fp32 [M]
  *   wq       in  int8 [N,K]          w_scale in fp32 [N]

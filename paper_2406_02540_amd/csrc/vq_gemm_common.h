@@ -36,9 +36,11 @@ __device__ __forceinline__ unsigned clamp_u32(long v) {
 __device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
     const unsigned long long p = (unsigned long long)base;
     v4i r;
-    r[0] = (int)(unsigned)p;
-    r[1] = (int)(unsigned)(p >> 32) & 0xFFFF;
-    r[2] = (int)bytes;
+    // (base and size are the same for every lane of a wave: saying so keeps the descriptor in
+    // scalar registers, where the buffer instructions want it, however it was computed)
+    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)p);
+    r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)(p >> 32) & 0xFFFF);
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
     r[3] = (int)kRsrcFlags;
     return r;
 }
@@ -92,6 +94,14 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" : : : "memory");
 }
 
+// The same, but the newest N vector memory operations of this wave may stay in flight
+// (they complete in the order of issue: everything older has completed).
+template <int N>
+__device__ __forceinline__ void wait_loads_before_and_barrier() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
 // Barrier for LDS traffic only: loads in flight stay in flight.
 __device__ __forceinline__ void wait_lds_and_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory");
@@ -110,6 +120,26 @@ __device__ __forceinline__ v4i widen_nibbles(v2i p) {
         o[2 * d + 1] = (int)__builtin_amdgcn_perm(odd, even, 0x07030602u);  // k = 4,5,6,7
     }
     return o;
+}
+
+// The dequantization of two neighbouring outputs into one register of two fp16 values:
+//     y = fp16( a * s + float(bias) ),
+// the multiply-add exact and rounded once, to nearest even, straight to fp16 (the mixed-precision
+// multiply-add takes fp32 a and s and the fp16 bias as they are).  bias2 holds the two bias
+// values as they lie in memory (low half first).  Every GEMM kernel of the library narrows
+// through these, so that an output does not depend on which kernel computed it.
+__device__ __forceinline__ unsigned dequant_pair(float a0, float s0, float a1, float s1, unsigned bias2) {
+    unsigned d;
+    asm("v_fma_mixlo_f16 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(d) : "v"(a0), "v"(s0), "v"(bias2));
+    asm("v_fma_mixhi_f16 %0, %1, %2, %3 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "+v"(d) : "v"(a1), "v"(s1), "v"(bias2));
+    return d;
+}
+// The same without a scale (the fp16 comparison layer): y = fp16( a + float(bias) ), rounded once.
+__device__ __forceinline__ unsigned add_bias_pair(float a0, float a1, unsigned bias2) {
+    unsigned d;
+    asm("v_fma_mixlo_f16 %0, %1, 1.0, %2 op_sel:[0,0,0] op_sel_hi:[0,0,1]" : "=v"(d) : "v"(a0), "v"(bias2));
+    asm("v_fma_mixhi_f16 %0, %1, 1.0, %2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "+v"(d) : "v"(a1), "v"(bias2));
+    return d;
 }
 
 // Returns v unchanged but opaque to the optimiser: what is derived from the result is

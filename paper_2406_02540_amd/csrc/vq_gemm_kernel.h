@@ -45,8 +45,10 @@
 //     retention (nontemporal): the operands keep the L2.
 //   - The kernel is persistent: one workgroup per CU walks a list of tiles.
 //     The first stage of the next tile is requested while the last stage of
-//     the current one is multiplied, and the epilogue (which stages through
-//     the buffer just consumed) runs while those loads are in flight.
+//     the current one is multiplied, its second stage right behind that stage's
+//     barrier, ahead of the epilogue's stores; the epilogue turns its blocks through
+//     a small LDS area of its own, so the waves go from it into the next tile without
+//     meeting at a barrier.
 //   - Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; each
 //     XCD gets a contiguous run of tiles, ordered in bands of 8 token tiles,
 //     and the workgroups of an XCD take them in turn, so that its L2 sees each
@@ -56,9 +58,10 @@
 // same whatever the tiling; the 4-bit path multiplies by 16 * w (nibble left in
 // the high half of the byte) and divides the sum by 16 exactly afterwards.
 //
-// The epilogue computes fp16_rne(fma_f32(float(acc) * x_scale, w_scale, bias)): one fp32
-// rounding fewer than three separate operations, so an output can differ from the
-// separately rounded value in the last fp16 place.
+// The epilogue computes fp16_rne(float(acc) * fp32(x_scale * w_scale) + bias): the product of
+// the two scales is rounded to fp32, the multiply-add is exact and rounded once, to fp16
+// (two vector instructions per output instead of four).  An output can differ from the
+// value of three separately rounded fp32 operations in the last fp16 place.
 //
 // W_BITS == 16 instantiates the same kernel for fp16 operands and fp32 sums
 // (v_mfma_f32_32x32x16_f16, the same 16 bytes of K per lane and operand): the FP16 layer
@@ -114,16 +117,18 @@ struct TileShape {
     static constexpr int kWLoaders = kSplitRoles ? kWaves - 8 : 8;
     static constexpr int kWPer8 = kTileC / 8 / kWLoaders;    // int8 (and fp16) W loads per loading wave
     static constexpr int kWPer4 = kTileC / 16 / kWLoaders;   // packed 4-bit W loads per loading wave
-    // Epilogue: a wave stages kFlushTb blocks of 32 tokens x 64 channels of fp16 at a time, in
-    // the stage buffers just consumed (the X buffer first, then the W buffer).
-    static constexpr int kFlushTb = (kWaves * TB * 4096 <= kXStage + kWStage) ? TB : ((kWaves * 8192 <= kXStage + kWStage) ? 2 : 1);
-    static constexpr int kEpiWave = kFlushTb * 4096;
-    static constexpr int kEpiInX = kXStage / kEpiWave;       // waves that stage in the X buffer
+    // Epilogue: every wave has a staging area of its own behind the stage buffers, 16 token
+    // rows x 128 B, through which half a block of 32 tokens x 64 channels of fp16 is turned at
+    // a time.  (The stage buffers themselves are busy: the next tile's first two stages land
+    // there while the epilogue runs.)
+    static constexpr int kEpiRows = 16;
+    static constexpr int kEpiWave = kEpiRows * 128;
+    static constexpr int kEpiBytes = kWaves * kEpiWave;
+    static constexpr int kStoresPerTile = TB * 4;            // 128-bit stores of a wave's epilogue
     static_assert(kTileT == 256, "scales are fetched by threads 0..255, one token each");
     static_assert(kTileC <= 256 && kWaves % 4 == 0 && kWaves >= 8, "tile shape");
     static_assert(kTileC / 8 % kWLoaders == 0 && kTileC / 16 % kWLoaders == 0, "W loads divide evenly");
-    static_assert((kWaves - kEpiInX) * kEpiWave <= kWStage || kWaves <= kEpiInX, "staging fits the consumed buffers");
-    static_assert(TB % kFlushTb == 0, "whole flushes");
+    static_assert(kLdsBytes + kScaleBytes + kEpiBytes <= 160 * 1024, "LDS of one CU");
 };
 
 // Where a tile sits in the output (wave-uniform).
@@ -160,9 +165,9 @@ template <class S, int W_BITS, bool K_TAIL, bool GENERIC>
 __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant(const GemmArgs a) {
     constexpr int TB = S::TB;
     constexpr int kXStage = S::kXStage, kWStage = S::kWStage, kLdsBytes = S::kLdsBytes;
-    __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes + kScaleBytes];
-    // layout: [X buffer 0][X buffer 1][W buffer 0][W buffer 1][scales]; a W buffer is
-    // [rows][128 B] of int8 or, for 4-bit weights, [rows][64 B] of nibbles.
+    __shared__ __attribute__((aligned(1024))) int8_t lds[kLdsBytes + kScaleBytes + S::kEpiBytes];
+    // layout: [X buffer 0][X buffer 1][W buffer 0][W buffer 1][scales][epilogue staging]; a W
+    // buffer is [rows][128 B] of int8 or, for 4-bit weights, [rows][64 B] of nibbles.
     int8_t* const lds_x = lds;
     int8_t* const lds_w = lds + kStages * kXStage;
     const unsigned lds_x_addr = (unsigned)(uintptr_t)(lds_ptr)lds_x;
@@ -198,27 +203,54 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
     // (4 (g%2) + l/16) % 8 for all of them.
     // Packed 4-bit tile [rows][64 B]: 16 rows x 64 B per load, lane l = row l/4,
     // physical chunk l%4 holding logical chunk (l%4) ^ ((row/4)%4) = (l%4) ^ (l/16).
-    auto decode_tile = [&](int idx, TilePos& t, TileLoads& ld) {
-        const int l = opaque(lane);
+    // The tiles of an XCD are numbered band by band (kBand token tiles), column by column
+    // within a band, token tile by token tile within a column.  A workgroup's tiles lie
+    // a.slots apart: the first one is located by division, the later ones by stepping.
+    const int band_tiles = kBand * a.tiles_c;
+    int dec_band, dec_in_band;   // where the tile decoded last sits (wave-uniform)
+    bool ld_full = false;        // that tile was a full one: its per-lane offsets hold for any full tile
+    auto locate_tile = [&](int idx) {
         const int logical = (blockIdx.x % kXcds) * a.tiles_per_xcd + idx;
-        const int band_tiles = kBand * a.tiles_c;
-        const int band = logical / band_tiles;
-        const int band_first = band * kBand;
+        dec_band = logical / band_tiles;
+        dec_in_band = logical - dec_band * band_tiles;
+    };
+    auto step_tile = [&]() {
+        dec_in_band += a.slots;
+        while (dec_in_band >= band_tiles) {
+            dec_in_band -= band_tiles;
+            ++dec_band;
+        }
+    };
+    auto decode_tile = [&](TilePos& t, TileLoads& ld) {
+        const int band_first = dec_band * kBand;
         const int band_rows = min(a.tiles_t - band_first, kBand);
-        const int in_band = logical - band * band_tiles;
-        t.tok0 = (long)(band_first + in_band % band_rows) * S::kTileT;
-        t.ch0 = (long)(in_band / band_rows) * S::kTileC;
+        int row, col;
+        if (band_rows == kBand) {
+            row = dec_in_band % kBand;
+            col = dec_in_band / kBand;
+        } else {  // the last band of a matrix whose token tiles are not a multiple of kBand
+            row = dec_in_band % band_rows;
+            col = dec_in_band / band_rows;
+        }
+        t.tok0 = (long)(band_first + row) * S::kTileT;
+        t.ch0 = (long)col * S::kTileC;
         t.rows_x = (int)min((long)S::kTileT, a.M - t.tok0);
         t.rows_w = (int)min((long)S::kTileC, a.N - t.ch0);
         ld.rsrc_x = make_rsrc(a.xq + t.tok0 * K, clamp_u32((a.M - t.tok0) * (long)K));
         ld.rsrc_w = make_rsrc((const int8_t*)a.w + t.ch0 * (K / kWDiv),
                               clamp_u32((a.N - t.ch0) * (long)(K / kWDiv)));
+        // The per-lane offsets are relative to the tile and clamp rows past the matrix: between
+        // two full tiles they do not change.  (Rows < 256 and row lengths < 2^24: 24-bit products.)
+        const bool full = t.rows_x == S::kTileT && t.rows_w == S::kTileC;
+        if (full && ld_full) return;
+        ld_full = full;
+        const int l = opaque(lane);
         if (loads_x) {
             const int ld_chunk16 = ((l & 7) ^ ((4 * (wave & 1) + (l >> 4)) & 7)) << 4;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = (wave + 8 * j) * 8 + (l >> 3);
-                ld.voff_x[j] = min(r, t.rows_x - 1) * K + ld_chunk16;
+                ld.voff_x[j] = __mul24(min(r, t.rows_x - 1), K) + ld_chunk16;
             }
         }
         if (loads_w) {
@@ -228,9 +260,9 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
             for (int j = 0; j < kWPer; ++j) {
                 const int g = w_loader + S::kWLoaders * j;   // row group of this load
                 if (W_BITS != 4)
-                    ld.voff_w[j] = min(w_row_to_channel(g * 8 + (l >> 3)), t.rows_w - 1) * K + ld_chunk16;
+                    ld.voff_w[j] = __mul24(min(w_row_to_channel(g * 8 + (l >> 3)), t.rows_w - 1), K) + ld_chunk16;
                 else
-                    ld.voff_w[j] = min(w_row_to_channel(g * 16 + (l >> 2)), t.rows_w - 1) * (K / 2) + ld_chunk16_w4;
+                    ld.voff_w[j] = __mul24(min(w_row_to_channel(g * 16 + (l >> 2)), t.rows_w - 1), K / 2) + ld_chunk16_w4;
             }
         }
     };
@@ -284,8 +316,11 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
     if (!tile_exists(idx)) return;  // uniform per workgroup
     TilePos cur;   // the tile being multiplied
     TileLoads ld;  // the tile whose stages are being requested (the next one during the last stage)
-    decode_tile(idx, cur, ld);
+    locate_tile(idx);
+    decode_tile(cur, ld);
     int buf = 0;  // LDS buffer of the stage about to be multiplied
+    bool requested1 = false;        // the current tile's second stage was requested before the previous epilogue
+    bool stores_in_flight = false;  // this wave wrote outputs in the previous epilogue (kStoresPerTile stores)
     issue_all(ld, 0, 0);
     wait_loads_and_barrier();  // the first tile's first stage (later ones arrive behind an epilogue)
 
@@ -333,14 +368,18 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
         // every wave of the CU would sit idle there).  Compile-time flags: FIRST = the tile's
         // first stage (nothing deferred to run; its first K step starts the accumulators from
         // a constant zero), LAST = its last one (nothing is deferred past the epilogue).
-        auto stage = [&](const int it, auto first_tag, auto last_tag) __attribute__((always_inline)) {
+        // `requested`: the loads this stage would issue are already in flight.
+        auto stage = [&](const int it, auto first_tag, auto last_tag, const bool requested) __attribute__((always_inline)) {
             constexpr bool FIRST = decltype(first_tag)::value;
             constexpr bool LAST = decltype(last_tag)::value;
             // what to request while this stage is multiplied: the next stage of this tile,
             // or the first stage of the next tile
             const bool more = it + 1 < nk;
-            const bool fetch = more || has_next;
-            if (!more && has_next) decode_tile(next_idx, nxt, ld);
+            const bool fetch = (more || has_next) && !requested;
+            if (!more && has_next) {
+                step_tile();
+                decode_tile(nxt, ld);
+            }
             const int fk0 = more ? (it + 1) * kTileK : 0;
 
             const int8_t* xs = lds_x + buf * kXStage;
@@ -423,65 +462,70 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
             // The stage requested above has landed for every wave and every wave is done
             // reading this one.  After the last stage this also says: the scales are in LDS,
             // the next tile's first stage is in, and only stores can be outstanding later.
-            wait_loads_and_barrier();
+            // (A stage whose loads were requested before the previous tile's epilogue has this
+            // wave's stores of that epilogue behind them, and nothing else: the stores may stay
+            // in flight.  Vector memory operations complete in the order they were issued.)
+            if (requested && stores_in_flight)
+                wait_loads_before_and_barrier<S::kStoresPerTile>();
+            else
+                wait_loads_and_barrier();
             buf ^= 1;
         };
+        constexpr std::true_type kYes{};
+        constexpr std::false_type kNo{};
         if (!wave_live) {
             // nothing to multiply in this tile, but this wave's share of the loads is needed
 #pragma unroll 1
             for (int it = 0; it < nk; ++it) {
                 const bool more = it + 1 < nk;
-                if (!more && has_next) decode_tile(next_idx, nxt, ld);
-                if (more || has_next) issue_all(ld, buf ^ 1, more ? (it + 1) * kTileK : 0);
+                if (!more && has_next) {
+                    step_tile();
+                    decode_tile(nxt, ld);
+                }
+                if ((more || has_next) && !(it == 0 && requested1)) issue_all(ld, buf ^ 1, more ? (it + 1) * kTileK : 0);
                 if (!more) park_scales();
                 wait_loads_and_barrier();
                 buf ^= 1;
             }
         } else if (nk == 1) {
-            stage(0, std::true_type{}, std::true_type{});
+            stage(0, kYes, kYes, false);
         } else {
-            stage(0, std::true_type{}, std::false_type{});
+            stage(0, kYes, kNo, requested1);
 #pragma unroll 1
-            for (int it = 1; it < nk - 1; ++it) stage(it, std::false_type{}, std::false_type{});
-            stage(nk - 1, std::false_type{}, std::true_type{});
+            for (int it = 1; it < nk - 1; ++it) stage(it, kNo, kNo, false);
+            stage(nk - 1, kNo, kYes, false);
         }
-        // `buf` now names the buffer that holds the next tile's first stage; the other one
-        // (the last stage multiplied) becomes the epilogue's staging area.
+        // `buf` now names the buffer that holds the next tile's first stage and the other one
+        // is free: the next tile's second stage is requested into it here, ahead of the
+        // epilogue's stores, so that it arrives while the epilogue computes.
+        requested1 = has_next && nk >= 2;
+        if (requested1) issue_all(ld, buf ^ 1, kTileK);
+        stores_in_flight = false;
 
         // ---- epilogue ------------------------------------------------------------
         // Lane (h = lane/32, t = lane%32) holds, for each of its TB token blocks, the
         // 32 channels chl .. chl+31: accumulator block b, register r <-> chl + 16 b + r.
         if (wave_live) {
+            stores_in_flight = !GENERIC;
             const int el = opaque(lane);  // (the epilogue's per-lane values are not kept across the mainloop)
             const int h = el >> 5;
             const long chw = cur.ch0 + wave_c * 64;  // first channel of this wave
-            // the 4-bit path accumulated 16 * w: fold the exact 1/16 into the channel scale
-            const float wmul = (W_BITS == 4) ? 0.0625f : 1.0f;
-            float wsc[32], bsc[32];
+            // the 4-bit path accumulated 16 * w: the exact 1/16 rides on the token scale
+            const float xmul = (W_BITS == 4) ? 0.0625f : 1.0f;
+            // channel scales are read from LDS where they are used (32 registers fewer across
+            // the epilogue); the bias is kept as it is stored, two fp16 values to a register
             const int8_t* sc_w = lds_sc + (wave_c * 64 + 32 * h) * 4;
             const int8_t* sc_b = lds_sc + 1024 + (wave_c * 64 + 32 * h) * 2;
+            v4i bias2[4];
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                const v4f sv = *(const v4f*)(sc_w + 16 * g);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) wsc[4 * g + e] = sv[e] * wmul;
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const half8 bv = *(const half8*)(sc_b + 16 * g);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) bsc[8 * g + e] = (float)bv[e];
-            }
+            for (int g = 0; g < 4; ++g) bias2[g] = *(const v4i*)(sc_b + 16 * g);
 
-            // staging: [32 kFlushTb token rows][128 B], 16-byte chunks XOR-ed by (row/2)%8; the first
-            // waves use the X buffer just consumed, the others the W buffer.
-            // (byte offsets into `lds`; the staging areas are 4 KiB aligned, so the XORs below
-            // stay inside the chunk bits)
-            constexpr int kFlushTb = S::kFlushTb;
-            const int stg = (wave < S::kEpiInX ? (buf ^ 1) * kXStage + wave * S::kEpiWave
-                                               : kStages * kXStage + (buf ^ 1) * kWStage + (wave - S::kEpiInX) * S::kEpiWave);
-            // writes: this lane's token row (el%32 of its block), logical chunk 4h+g
-            const int st_wr = stg + (el & 31) * 128 + ((4 * h ^ ((el >> 1) & 7)) << 4);
+            // staging: [16 token rows][128 B] of this wave, 16-byte chunks XOR-ed by (row/2)%8
+            // (byte offsets into `lds`; the area is 1 KiB aligned, so the XORs below stay inside
+            // the chunk bits)
+            const int stg = kLdsBytes + kScaleBytes + wave * S::kEpiWave;
+            // writes: this lane's token row (el%16 of its half block), logical chunk 4h+g
+            const int st_wr = stg + (el & 15) * 128 + ((4 * h ^ ((el >> 1) & 7)) << 4);
             // flush reads: row 8i + el/8, logical chunk el%8 (its XOR mask alternates with i)
             const int st_rd = stg + (el >> 3) * 128 + (((el & 7) ^ (el >> 4)) << 4);
             // Flush stores are range-checked buffer stores relative to the tile's first token
@@ -495,35 +539,36 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
                 const int tl = wave_t * 32 * TB + tb * 32 + (el & 31);  // token within the tile
-                const float xsc = *(const float*)(lds_sc + 2048 + tl * 4);
+                const float xsc = *(const float*)(lds_sc + 2048 + tl * 4) * xmul;
+                v4i out[4];  // eight fp16 outputs each
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int b = g >> 1, r0 = (g & 1) * 8;
-                    half8 out;
+                    // y = fp16(float(acc) * (x_scale * w_scale) + bias): the product of the two
+                    // scales rounded to fp32, the rest exact and rounded once (dequant_pair)
+                    float sp[8];
+                    if (W_BITS != 16) {
+                        const v4f s0 = *(const v4f*)(sc_w + 32 * g), s1 = *(const v4f*)(sc_w + 32 * g + 16);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        float y;
-                        if (W_BITS == 16) {  // the fp32 sum of the fp16 products, plus the bias
-                            y = (float)acc[b][tb][r0 + e] + bsc[8 * g + e];
-                        } else {
-                            const float f = (float)acc[b][tb][r0 + e] * xsc;
-                            y = __builtin_fmaf(f, wsc[8 * g + e], bsc[8 * g + e]);
-                        }
-                        // keep the fp32 result as such: the narrowing below then is a plain
-                        // round-to-nearest-even of it in every variant of this kernel (a fused
-                        // multiply-add-narrow instruction would round only once)
-                        asm("" : "+v"(y));
-                        out[e] = (_Float16)y;
+                        for (int e = 0; e < 4; ++e) sp[e] = xsc * s0[e], sp[4 + e] = xsc * s1[e];
                     }
-                    if (!GENERIC) {
-                        *(half8*)(lds + (st_wr ^ (g << 4)) + (tb % kFlushTb) * 4096) = out;
-                    } else if (tl < cur.rows_x) {
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2) {
+                        if (W_BITS == 16)  // the fp32 sum of the fp16 products, plus the bias
+                            out[g][e / 2] = (int)add_bias_pair((float)acc[b][tb][r0 + e], (float)acc[b][tb][r0 + e + 1],
+                                                               (unsigned)bias2[g][e / 2]);
+                        else
+                            out[g][e / 2] = (int)dequant_pair((float)acc[b][tb][r0 + e], sp[e], (float)acc[b][tb][r0 + e + 1],
+                                                              sp[e + 1], (unsigned)bias2[g][e / 2]);
+                    }
+                    if (GENERIC && tl < cur.rows_x) {
                         const long tok = cur.tok0 + tl;
                         const long c0 = chw + 32 * h + 8 * g;
+                        const half8 oh = (half8)out[g];  // (reinterprets the bits)
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
                             if (c0 + e < a.N) {
-                                a.y[tok * a.N + c0 + e] = out[e];
+                                a.y[tok * a.N + c0 + e] = oh[e];
                                 if (a.acc_out) {
                                     const int v = (int)acc[b][tb][r0 + e];
                                     a.acc_out[tok * a.N + c0 + e] = (W_BITS == 4) ? (v >> 4) : v;
@@ -532,29 +577,40 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
                         }
                     }
                 }
-                if (!GENERIC && (tb % kFlushTb) == kFlushTb - 1) {
-                    // 32 kFlushTb token rows x 128 B are staged: write them out, a full line per 8 lanes.
-                    // Only this wave touches its staging area and the LDS operations of a wave
-                    // execute in order; the fences only keep the compiler from reordering them.
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    v4i rows[4 * kFlushTb];
+                if (!GENERIC) {
+                    // The block goes out in two halves of 16 token rows: the lanes that hold them
+                    // stage their 64 bytes each, then the wave writes the 16 rows x 128 B out, a
+                    // full line per 8 lanes.  Only this wave touches its staging area and the LDS
+                    // operations of a wave execute in order; the fences only keep the compiler
+                    // from reordering them.
 #pragma unroll
-                    for (int i = 0; i < 4 * kFlushTb; ++i)
-                        rows[i] = *(const v4i*)(lds + (st_rd ^ ((i & 1) << 6)) + i * 1024);
+                    for (int p = 0; p < 2; ++p) {
+                        if (((el >> 4) & 1) == p) {
 #pragma unroll
-                    for (int i = 0; i < 4 * kFlushTb; ++i)
-                        __builtin_amdgcn_raw_buffer_store_b128(
-                            rows[i], rsrc_y,
-                            y_off0 + (unsigned)(((tb - (kFlushTb - 1)) * 32 + i * 8) * a.N * 2), 0, 2 /* nontemporal */);
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
+                            for (int g = 0; g < 4; ++g) *(v4i*)(lds + (st_wr ^ (g << 4))) = out[g];
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        v4i rows[2];
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) rows[i] = *(const v4i*)(lds + (st_rd ^ (i << 6)) + i * 1024);
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+                            __builtin_amdgcn_raw_buffer_store_b128(
+                                rows[i], rsrc_y, y_off0 + (unsigned)((tb * 32 + p * 16 + i * 8) * a.N * 2), 0,
+                                2 /* nontemporal */);
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
                 }
             }
         }
         if (!has_next) break;
-        // every wave has left its staging area: the next tile's second stage may land there
-        wait_lds_and_barrier();
+        // A one-stage tile parks its scales before its only barrier: nobody may still be
+        // reading this tile's.  (Otherwise the waves go on without meeting: every wave stages
+        // in an area of its own, and a barrier of the next tile's first stage comes before its
+        // scales are parked.)
+        if (nk == 1) wait_lds_and_barrier();
         cur = nxt;
         idx = next_idx;
     }

@@ -164,17 +164,24 @@ __global__ __launch_bounds__(kThreadsS) void gemm_i8_dequant_small(const SmallAr
     const bool vec = (a.N % 8) == 0;
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
-        half8 out;
         int iv[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int v = acc[8 * g + e];
-            iv[e] = (W_BITS == 4) ? (v >> 4) : v;
-            const float f = (float)v * xsc;
-            float y = __builtin_fmaf(f, wraw[8 * g + e] * wmul, a.bias ? (float)braw[8 * g + e] : 0.0f);
-            asm("" : "+v"(y));  // the narrowing is a plain round-to-nearest-even of the fp32 value
-            out[e] = (_Float16)y;
+        for (int e = 0; e < 8; ++e) iv[e] = (W_BITS == 4) ? (acc[8 * g + e] >> 4) : acc[8 * g + e];
+        // y = fp16(float(acc) * (x_scale * w_scale) + bias), as in the large-tile kernel: the
+        // product of the scales in fp32 (the exact 1/16 of the 4-bit path on the token scale),
+        // the rest exact and rounded once
+        v4i outv;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float s0 = (xsc * wmul) * wraw[8 * g + e], s1 = (xsc * wmul) * wraw[8 * g + e + 1];
+            unsigned b2 = 0;
+            if (a.bias) {
+                const _Float16 pair[2] = {braw[8 * g + e], braw[8 * g + e + 1]};
+                __builtin_memcpy(&b2, pair, 4);
+            }
+            outv[e / 2] = (int)dequant_pair((float)acc[8 * g + e], s0, (float)acc[8 * g + e + 1], s1, b2);
         }
+        const half8 out = (half8)outv;  // (reinterprets the bits)
         if (vec) {
             if (chl + 8 * g < a.N) {
                 *(half8*)(yrow + 8 * g) = out;

@@ -156,6 +156,34 @@ def test_gemm_parity(vq, oracle, M, N, K, bits):
     say(f"  max rel err {worst:.2e}, fp16 bit-identical: {exact}")
 
 
+@pytest.mark.parametrize("bits,M,N,K", [(8, 700, 392, 1184), (4, 700, 392, 1184), (8, 300, 136, 224),
+                                        (8, 2900, 2824, 1152), (4, 2900, 2824, 1152), (8, 2891, 2824, 144)])
+def test_dequantization_rounds_once(vq, oracle, bits, M, N, K):
+    """The rounding the header states for the epilogue, to the bit, in every GEMM kernel (small
+    tiles, 256 x 192, 256 x 256): s = fp32(x_scale * w_scale), y = fp16(float(acc) * s + bias) with
+    the multiply-add exact.  The host evaluates it in fp64, where acc * s is exact (24 + 24 bits)
+    and the sum with the bias is off by at most 2^-53 relative: a double rounding through fp64
+    could only differ for a sum within 2^-41 fp16 ulps of a tie, which these draws do not hit."""
+    say(f"dequantization rounding w{bits}a8 M={M} N={N} K={K}")
+    g = np.random.default_rng(5150 + M + N + K + bits)
+    qmax = 127 if bits == 8 else 7
+    xq = g.integers(-127, 128, (M, K), dtype=np.int8)
+    wq = g.integers(-qmax, qmax + 1, (N, K), dtype=np.int8)
+    xs = np.exp(g.uniform(-8, -2, M)).astype(np.float32)
+    ws = np.exp(g.uniform(-10, -5, N)).astype(np.float32)
+    b = g.normal(0, 0.01, N).astype(np.float16)
+    acc = oracle.gemm_i8(xq, wq)
+    assert np.abs(acc).max() < 2 ** 24  # float(acc) is exact
+    wdev = wq if bits == 8 else oracle.pack_int4(wq)
+    gemm = vq.vq_gemm_w8a8 if bits == 8 else vq.vq_gemm_w4a8
+    y = host(gemm(dev(xq), dev(xs), dev(wdev), dev(ws), dev(b)))
+    torch.cuda.synchronize()
+    s = (xs[:, None] * ws[None, :]).astype(np.float32)            # one fp32 rounding
+    want = (acc.astype(np.float64) * s.astype(np.float64) + b.astype(np.float64)[None, :]).astype(np.float16)
+    differ = int((y.view(np.uint16) != want.view(np.uint16)).sum())
+    assert differ == 0, f"{differ} of {y.size} outputs are not the singly rounded value"
+
+
 def test_gemm_without_bias_and_saturated_sums(vq, oracle):
     say("gemm no bias / saturation")
     _gemm_case(vq, oracle, 70, 40, 256, 8, seed=5, bias=False)
