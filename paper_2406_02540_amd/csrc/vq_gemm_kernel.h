@@ -97,6 +97,7 @@ constexpr int kStages = 2;
 constexpr int kScaleBytes = 3 * 1024;       // w_scale[256] fp32 | bias[256] fp16 (+pad) | x_scale[256] fp32
 constexpr int kBand = 8;                    // token tiles per band in the tile order
 constexpr int kXcds = 8;
+constexpr int kTouchRounds = 4;             // weight lines asked for up front: at most 4 x 8 KiB per wave (64 MiB per 256 CUs)
 
 // WT x WC wavefronts of (32 TB) tokens x 64 channels.
 template <int WT_, int WC_, int TB_>
@@ -322,7 +323,25 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
     bool requested1 = false;        // the current tile's second stage was requested before the previous epilogue
     bool stores_in_flight = false;  // this wave wrote outputs in the previous epilogue (kStoresPerTile stores)
     issue_all(ld, 0, 0);
+    // Every line of the weight matrix is asked for once, here, by the whole grid (one dword per
+    // 128-byte line and lane, 8 KiB per wave and round): the weights are a few MB that every XCD
+    // walks through completely, and a column's panel is otherwise first asked for by the eight
+    // CUs that need it at that moment, which then wait out the memory latency at every stage of
+    // their tile.  Fetched up front the lines are in the memory-side cache when their column's
+    // turn comes.  (Range-checked loads: lanes past the end of the matrix fetch nothing.)
+    int touched = 0;
+    {
+        const long w_bytes = (long)a.N * (K / kWDiv);
+        const __amdgpu_buffer_rsrc_t rsrc_all = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<void*>(a.w), 0, (int)clamp_u32(w_bytes), kRsrcFlags);
+        const unsigned per_round = gridDim.x * (unsigned)S::kWaves * 8192u;
+        unsigned off = (blockIdx.x * (unsigned)S::kWaves + (unsigned)wave) * 8192u + (unsigned)lane * 128u;
+#pragma unroll 1
+        for (int i = 0; i < kTouchRounds && (long)i * per_round < w_bytes; ++i, off += per_round)
+            touched ^= __builtin_amdgcn_raw_buffer_load_b32(rsrc_all, (int)off, 0, 0);
+    }
     wait_loads_and_barrier();  // the first tile's first stage (later ones arrive behind an epilogue)
+    asm volatile("" : : "v"(touched));  // (the fetched dwords are not used; they have arrived by now)
 
     // Invariant at the top of a stage: its operands have landed in buffer `buf` for every
     // wave, and nobody reads or writes the other buffer any more.
