@@ -329,19 +329,23 @@ __global__ __launch_bounds__(S::kThreads, S::kWavesPerSimd) void gemm_i8_dequant
     // CUs that need it at that moment, which then wait out the memory latency at every stage of
     // their tile.  Fetched up front the lines are in the memory-side cache when their column's
     // turn comes.  (Range-checked loads: lanes past the end of the matrix fetch nothing.)
-    int touched = 0;
+    int touched[kTouchRounds];
     {
         const long w_bytes = (long)a.N * (K / kWDiv);
         const __amdgpu_buffer_rsrc_t rsrc_all = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<void*>(a.w), 0, (int)clamp_u32(w_bytes), kRsrcFlags);
         const unsigned per_round = gridDim.x * (unsigned)S::kWaves * 8192u;
-        unsigned off = (blockIdx.x * (unsigned)S::kWaves + (unsigned)wave) * 8192u + (unsigned)lane * 128u;
-#pragma unroll 1
-        for (int i = 0; i < kTouchRounds && (long)i * per_round < w_bytes; ++i, off += per_round)
-            touched ^= __builtin_amdgcn_raw_buffer_load_b32(rsrc_all, (int)off, 0, 0);
+        const unsigned off = (blockIdx.x * (unsigned)S::kWaves + (unsigned)wave) * 8192u + (unsigned)lane * 128u;
+#pragma unroll
+        for (int i = 0; i < kTouchRounds; ++i) {
+            touched[i] = 0;
+            if ((long)i * per_round < w_bytes)  // (uniform; all rounds are in flight together)
+                touched[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_all, (int)(off + i * per_round), 0, 0);
+        }
     }
     wait_loads_and_barrier();  // the first tile's first stage (later ones arrive behind an epilogue)
-    asm volatile("" : : "v"(touched));  // (the fetched dwords are not used; they have arrived by now)
+#pragma unroll
+    for (int i = 0; i < kTouchRounds; ++i) asm volatile("" : : "v"(touched[i]));  // (not used; they have arrived by now)
 
     // Invariant at the top of a stage: its operands have landed in buffer `buf` for every
     // wave, and nobody reads or writes the other buffer any more.

@@ -224,7 +224,7 @@ def test_identity_weights_select_the_activations(vq):
 
 @pytest.mark.parametrize("bits,K,M,N", [(8, 4608, 2900, 2824), (4, 4608, 2900, 2824), (8, 1168, 2900, 2824),
                                         (4, 1184, 2900, 2824), (8, 1152, 5003, 5000), (4, 1152, 5003, 5000),
-                                        (8, 1168, 5003, 5000)])
+                                        (8, 1168, 5003, 5000), (8, 4608, 2064, 4616)])
 def test_line_store_variant_shows_its_integer_sums(vq, oracle, bits, K, M, N):
     """The kernel variants the benchmark times (no copy of the sums, whole-line stores, the
     persistent large-tile kernels: 2900 x 2824 takes the 256 x 192 tile, 5003 x 5000 the
@@ -232,7 +232,8 @@ def test_line_store_variant_shows_its_integer_sums(vq, oracle, bits, K, M, N):
     between: activations sparse in {-1, 0, 1} keep every sum below 2048 in magnitude, so with
     unit scales and no bias the fp16 output IS the integer sum (appendix "Hardware implementation
     of quantized linear layers": integer sum first, scales afterwards).  K = 4608 and 1152 are a
-    whole number of K stages, the other K are not."""
+    whole number of K stages, the other K are not; the last case has 21 MB of weights, more than
+    one round of the lines the kernel asks for at its start."""
     say(f"gemm w{bits}a8 line-store variant, exact integers, M={M} N={N} K={K}")
     g = np.random.default_rng(4100 + bits + K)
     qmax = 127 if bits == 8 else 7
